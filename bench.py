@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched INR decode hot path on one MI355X.
+
+A "step" is one rinr_decode_batch_ex call over the whole batch of the chosen workload
+(gather -> expand/dequant -> coordinates -> first / hidden / output layers -> NCHW store)
+with the packed store, the image ids and the output tensors already resident in HBM.
+Default workload: 256 images of 224x224, MLP 2->64 (x6 sine layers)->3, 8-bit hidden
+layers, 70 % pruned, uint8 + fp32 NCHW outputs.  Data is synthetic (seeded).
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 FLOP/clk x 2.4 GHz)
+
+
+def host_threads() -> int:
+    n = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit() and int(env) > 0:
+        n = min(n, int(env))
+    return n
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4, the headline one)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile", type=int, default=0, help="experiment: MFMA tile rows for widths 32/64 (16 or 32)")
+    ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--threads", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build decodes on one GPU only (images are independent; see DESIGN.md "
+              "for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2306_16699_amd import rinr, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    rinr.lib()
+    if args.tile:
+        rinr.tune(0, args.tile)
+    if args.blocks_per_cu:
+        rinr.tune(1, args.blocks_per_cu)
+    if args.threads:
+        rinr.tune(2, args.threads)
+
+    w = synth.workload(args.config)
+    blob = rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)
+    st = rinr.Store(blob)
+    ids = torch.from_numpy(w.image_ids).cuda()
+    n, H, W = w.n, w.H, w.W
+    out = torch.empty((n, 3, H, W), dtype=torch.float32, device="cuda")
+    out8 = torch.empty((n, 3, H, W), dtype=torch.uint8, device="cuda") if w.out_u8 else None
+    dtype = rinr.OUT_F32_AND_U8 if w.out_u8 else rinr.OUT_F32
+
+    def step():
+        st.decode_batch_ex(ids, H, W, dtype, 0, out=out, out_u8=out8)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                      # same stream the library launches on (torch's current stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / args.steps
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    assert st.status() == 0
+    info = st.last_launch_info()
+
+    pixels = n * H * W
+    flop_px = np.array([synth.dense_flop_per_pixel(w.models[int(i)]) for i in w.image_ids], dtype=np.float64)
+    flops = float(flop_px.sum()) * H * W
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"decode_cfg{args.config}_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    res = {
+        "metric": "decoded pixels/sec (and images/sec) on 1 MI355X; % of MFMA/VALU FLOP peak",
+        "value": pixels / (wall_ms * 1e-3),
+        "unit": "pixels/s",
+        "images_per_s": n / (wall_ms * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "images": n, "H": H, "W": W,
+                   "outputs": "fp32+uint8 NCHW" if w.out_u8 else "fp32 NCHW",
+                   "flop_per_pixel_mean": float(flop_px.mean()),
+                   "launch": info},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
+                     "kernel_ms": kern_ms, "flop_per_launch": flops},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        cores = host_threads()
+        per_img_s = float(flop_px.mean()) * H * W / 2.0e9        # the scalar fp64 oracle runs near 2 GFLOP/s per core
+        n_s = int(max(1, min(n, round(15.0 * cores / max(per_img_s, 1e-4)))))   # about 15 s of wall time
+        sample = w.image_ids[:n_s]
+        tc = time.perf_counter()
+        oracle.decode(w.models, sample, H, W, w.w0, w.coord_lo, w.coord_hi, want_u8=w.out_u8, n_threads=cores)
+        dt = time.perf_counter() - tc
+        res["cpu_baseline"] = {"value": n_s * H * W / dt, "unit": "pixels/s", "cores": cores, "kind": "oracle",
+                               "sample": f"first {n_s} of {n} slots, all pixels, fp64 C oracle with OpenMP over images, {dt:.1f} s"}
+    st.close()
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

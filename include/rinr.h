@@ -1,0 +1,179 @@
+/* rinr — batched on-GPU decode of an INR-compressed image dataset (MI355X / gfx950).
+ *
+ * Every image is its own small sine-activated coordinate MLP (paper Sec. III-A):
+ * input the pixel's normalised (x, y), output (R, G, B).  The whole dataset is
+ * uploaded to GPU memory once in weight form (Sec. III-B) and a batch of image
+ * ids is decoded on the fly, at any resolution, into an NCHW RGB tensor that
+ * stays on the GPU (Sec. III-B).  Weights may be pruned with a mask (Sec. IV-A)
+ * and stored as integer codes with a per-layer affine map; the paper quantises
+ * the hidden layers to 8 bits and keeps the first and last layer fp32
+ * (Sec. IV-B).  Activation: sin with frequency w0 = 30 (Sec. VI-A).
+ *
+ * Plain C ABI.  Every function returns 0 (RINR_OK) or a negative RINR_E_* code;
+ * nothing throws across the boundary.  "host" / "device" on a pointer says which
+ * memory it must point to.  The caller owns every buffer it passes; the library
+ * owns only the rinr_store handle (and one small device status word inside it).
+ */
+#ifndef RINR_H
+#define RINR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    RINR_OK = 0,
+    RINR_E_NULL = -1,        /* a required pointer is NULL                           */
+    RINR_E_ARG = -2,         /* a size or option is out of range                     */
+    RINR_E_MODEL = -3,       /* a model description breaks a rule listed at rinr_pack */
+    RINR_E_SIZE = -4,        /* buffer too small / size overflows                    */
+    RINR_E_FORMAT = -5,      /* blob header, index or a record is corrupt            */
+    RINR_E_UNSUPPORTED = -6, /* valid, but wider/deeper than the kernels are built for */
+    RINR_E_ALIGN = -7,       /* a device pointer is not aligned as required          */
+    RINR_E_HIP = -8          /* a HIP runtime call failed (see rinr_last_hip_error)  */
+};
+
+enum { RINR_MAX_WIDTH = 64,    /* widest hidden layer the decode kernels accept        */
+       RINR_MAX_LAYERS = 16 }; /* most linear layers per model                         */
+
+/* ---- host-side description of one model (input of rinr_pack) ---------------------
+ * Layer l computes y = W x + b with W stored [out][in] row-major (Sec. III-A MLP).
+ * All layers but the last are followed by sin(w0 * y); the last is linear. */
+typedef struct {
+    int32_t in, out;        /* 1..RINR_MAX_WIDTH; first layer in == 2, last out == 3   */
+    int32_t bits;           /* 0 = raw fp32 weights; 2..8 or 16 = integer codes         */
+    float scale;            /* w = scale * (code - zp) (Sec. IV-B); ignored if bits==0  */
+    int32_t zp;             /* 0 .. 2^bits - 1; ignored if bits == 0                    */
+    const void *weights;    /* host. bits==0: float[out*in]; bits<=8: uint8_t[out*in];
+                               bits==16: uint16_t[out*in]. One entry per weight, pruned
+                               ones included (their value is ignored).                   */
+    const uint8_t *mask;    /* host. NULL = dense; else out*in bits, bit k of the flat
+                               index k = o*in + i at byte k/8, bit k%8; 1 = kept,
+                               0 = pruned, i.e. the weight is exactly 0 (Sec. IV-A)      */
+    const float *bias;      /* host. float[out]; never pruned or quantised             */
+} rinr_layer_desc;
+
+typedef struct {
+    int32_t n_layers;               /* linear layers, 2..RINR_MAX_LAYERS (>= 1 sine layer) */
+    const rinr_layer_desc *layers;  /* host                                              */
+} rinr_model_desc;
+
+/* Store-wide decode constants.  NULL where accepted means {30, -1, 1}. */
+typedef struct {
+    float w0;                /* sine frequency (Sec. VI-A: 30)                          */
+    float coord_lo, coord_hi;/* pixel-centre grid spans [lo, hi] on both axes:
+                                x_j = lo + (hi-lo)(2j+1)/(2W), y_i likewise with H.
+                                The paper's text normalises to 0..1 (Sec. III-A);
+                                sine-network initialisations assume -1..1 (default).      */
+} rinr_store_opts;
+
+/* ---- packing: model descriptions -> one position-independent blob ---------------
+ * The blob is the dataset in "weight format": what is saved to disk and what is
+ * uploaded once to the GPU (Sec. III-B).  Little-endian; offsets, no pointers.
+ * Per layer it holds the mask (1 bit per weight), the codes of the KEPT weights
+ * only, in ascending flat index, as one LSB-first bit stream of `bits` per code
+ * (32 for raw fp32), and the fp32 biases.
+ *
+ * rinr_pack_size: *bytes = exact size rinr_pack will write.
+ * rinr_pack: writes the blob to host_blob (capacity `bytes`, must be >= that size).
+ * Both validate and return RINR_E_MODEL for: n_layers out of range; in/out out of
+ * range; first in != 2; last out != 3; out of layer l != in of layer l+1; bits not
+ * in {0, 2..8, 16}; zp outside [0, 2^bits); a kept code >= 2^bits; non-finite scale,
+ * bias or kept fp32 weight; NULL weights or bias.  RINR_E_ARG for n_models < 0 or
+ * non-finite / zero-span opts. */
+int rinr_pack_size(const rinr_model_desc *models, int64_t n_models, const rinr_store_opts *opts,
+                   size_t *bytes);
+int rinr_pack(const rinr_model_desc *models, int64_t n_models, const rinr_store_opts *opts,
+              void *host_blob, size_t bytes);
+
+/* Inverse of rinr_pack for ONE layer of ONE model, on the host (round-trip tests,
+ * tooling; not used by decode).  Reads a host copy of the blob and writes one entry
+ * per weight: codes_out (uint16_t[out*in], the stored code, or 0 where pruned; for
+ * bits == 0 unused and may be NULL), f32_out (float[out*in] dequantised weights,
+ * 0 where pruned), keep_out (uint8_t[out*in] 0/1), bias_out (float[out]).  Any
+ * output pointer may be NULL.  meta_out (may be NULL) receives
+ * {in, out, bits, zp, n_kept} and *scale_out the scale. */
+int rinr_unpack_layer(const void *host_blob, size_t bytes, int64_t model, int32_t layer,
+                      uint16_t *codes_out, float *f32_out, uint8_t *keep_out, float *bias_out,
+                      int32_t meta_out[5], float *scale_out);
+
+/* ---- device-resident store ------------------------------------------------------ */
+typedef struct rinr_store rinr_store;
+
+/* Opens a store over a blob already resident in device memory (device_blob, 16-byte
+ * aligned, `bytes` long).  host_blob, if not NULL, is a host copy of the same bytes and
+ * is validated in full (header, index, every record's offsets and sizes) without
+ * touching the device; if NULL the blob is copied back from the device once, here, for
+ * the same validation.  The store neither copies nor owns the blob: it must stay
+ * allocated and unchanged until rinr_store_close.  Must be called with the blob's
+ * device current.  Allocates the handle and an 8-byte device status word. */
+int rinr_store_open(const void *device_blob, const void *host_blob, size_t bytes, rinr_store **store);
+int rinr_store_close(rinr_store *store);
+int rinr_store_info(const rinr_store *store, int64_t *n_models, int32_t *max_width, int32_t *max_layers);
+
+/* ---- decode ------------------------------------------------------------------------ */
+enum { RINR_OUT_F32 = 1,           /* out: float [n][3][H][W], clamp(y, 0, 1)                 */
+       RINR_OUT_U8 = 2,            /* out: uint8 [n][3][H][W], rint(255 * clamp(y, 0, 1))     */
+       RINR_OUT_F32_AND_U8 = 3 };  /* out: float tensor, opts.out_u8: uint8 tensor            */
+enum { RINR_FLAG_NO_CLAMP = 1 };   /* fp32 output only: write the linear output unclamped     */
+
+typedef struct {
+    int32_t out_dtype;       /* RINR_OUT_*                                              */
+    int32_t flags;           /* RINR_FLAG_*                                             */
+    void *out_u8;            /* device; second output for RINR_OUT_F32_AND_U8, else NULL */
+} rinr_decode_opts;
+
+/* Decodes slots s = 0..n-1 (Sec. III-B: batch select + pixel- and image-parallel
+ * decode): slot s shows model image_ids[s] sampled on an H x W pixel-centre grid,
+ * written to out[s][c][i][j], c = 0,1,2 = R,G,B.  image_ids: device, int64[n],
+ * repeats allowed.  out: device, contiguous NCHW, 4-byte aligned for fp32.
+ * stream: a hipStream_t (NULL = the default stream).  Asynchronous: enqueues kernels
+ * on `stream` and returns; never synchronises, never reads the host copy of the blob.
+ * n == 0 is OK and launches nothing.  Host-detectable errors (NULL, n < 0, H or W <= 0,
+ * n*3*H*W overflowing int64 / a plane >= 2^31 pixels, misaligned out, bad out_dtype,
+ * NO_CLAMP with a uint8 output) are returned before anything is enqueued.  An id outside
+ * [0, n_models) cannot be seen from the host: that slot is written as zeros and a sticky
+ * device counter is incremented (read it with rinr_store_status).
+ * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL}. */
+int rinr_decode_batch(const rinr_store *models, const int64_t *image_ids, int32_t n,
+                      int32_t H, int32_t W, void *out, void *stream);
+int rinr_decode_batch_ex(const rinr_store *models, const int64_t *image_ids, int32_t n,
+                         int32_t H, int32_t W, void *out, const rinr_decode_opts *opts, void *stream);
+
+/* Synchronises `stream`, then reads (and leaves set) the count of out-of-range image
+ * ids seen by decodes on this store so far. */
+int rinr_store_status(const rinr_store *store, int64_t *bad_id_count, void *stream);
+
+/* Test hook for the expand/dequantise stage: runs the same device routine the decode
+ * kernels use to rebuild layer `layer` of model `id` from the packed record (mask,
+ * kept-code stream, affine map), reading the result back out of the kernel's on-chip
+ * layout, and writes float[out*in] (row-major [out][in], 0 where pruned) to device_out
+ * and, if bias_out is not NULL, float[out] biases.  No sine pre-scaling is applied, so
+ * the values are bit-comparable with scale * (code - zp) rounded once to fp32. */
+int rinr_debug_dequant(const rinr_store *store, int64_t id, int32_t layer, float *device_out,
+                       float *bias_out, void *stream);
+
+/* Grid the last decode on this store used (diagnostics / benchmarks):
+ * info[0] = kernel launches, info[1] = total workgroups, info[2] = threads per
+ * workgroup of the largest class, info[3] = its dynamic LDS bytes. */
+int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
+
+/* Process-wide tuning knobs for experiments; defaults are what the benchmarks use.
+ * knob 0: MFMA tile rows for padded widths 32 and 64: 16 (16x16x4 fp32) or 32 (32x32x2 fp32);
+ *         read at rinr_store_open.
+ * knob 1: grid target in workgroups per compute unit (1..1024).
+ * knob 2: threads per workgroup: 0 = by image size, or 256 / 512. */
+int rinr_tune(int knob, int value);
+
+const char *rinr_strerror(int code);
+/* hipError_t of the last failed HIP call on this thread (0 if none), as an int. */
+int rinr_last_hip_error(void);
+const char *rinr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RINR_H */

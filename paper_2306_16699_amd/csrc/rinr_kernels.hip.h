@@ -1,0 +1,402 @@
+// Device code of the decode path: on-chip weight layout, expand/dequantise stage and the
+// fused per-pixel MLP kernel.  gfx950 (CDNA4) only: 64-lane wavefronts, fp32 MFMA.
+//
+// Method (paper Sec. III-B): every pixel of every image of the batch is decoded in
+// parallel by pushing its normalised (x, y) through that image's own MLP.  Here one
+// workgroup owns (batch slot, range of pixel tiles).  It rebuilds the image's fp32
+// weights once into LDS from the packed record (mask + kept-code stream + affine map,
+// Sec. IV-A/B), then each wavefront walks its tiles of 64 pixels through all layers with
+// the activations held in registers from the first layer to the RGB store.
+//
+// Layers are evaluated transposed, Hout[width x pixels] = Wmat[width x width] * Hin, with
+// the weights as the MFMA A operand and pixels along the N axis.  The rows of an
+// accumulator tile that a lane owns are then exactly the contraction indices that lane
+// must supply as B operand of the next layer, provided the next layer's weights are laid
+// out in LDS with the matching permutation of k.  So bias (as the C operand of the first
+// k-step) and sin are applied in place and nothing crosses lanes between layers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "rinr_format.h"
+
+namespace rinr {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---- MFMA tile traits --------------------------------------------------------------------
+// TM = rows (and pixel columns) of one tile.  A lane is (n = lane % TM, g = lane / TM).
+//   A operand: lane supplies A[row n][k = g]      B operand: lane supplies B[k = g][col n]
+//   D tile   : RV registers per lane; register v holds row (v>>2)*4G + 4g + (v&3), column n
+template <int TM> struct Tile;
+template <> struct Tile<16> {
+    static constexpr int G = 4, RV = 4;
+    typedef f32x4 acc_t;
+    static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Tile<32> {
+    static constexpr int G = 2, RV = 16;
+    typedef f32x16 acc_t;
+    static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+};
+
+// ---- LDS layout of one expanded model --------------------------------------------------
+// WP = padded width (multiple of TM).  All indices are in floats.
+template <int TM, int WP> struct Layout {
+    typedef Tile<TM> T;
+    static constexpr int G = T::G, RV = T::RV;
+    static constexpr int MT = WP / TM;                 // row tiles per layer
+    static constexpr int MTS = (MT == 3) ? 4 : MT;     // stride of the per-lane A vector
+    static constexpr int KSTEPS = WP / G;              // MFMA k-steps of a hidden layer
+    static constexpr int FIRST = 64 * MTS;             // first layer: one k-step
+    static constexpr int HIDDEN = KSTEPS * 64 * MTS;   // one hidden layer
+    static constexpr int OUTW = 4 * WP;                // output layer, float4 per (g, r)
+    static_assert(WP % TM == 0, "padded width must be whole tiles");
+
+    // row-in-tile rr -> (lane group g, accumulator register v)
+    static __device__ __forceinline__ void split(int rr, int &g, int &v) {
+        if (TM == 16) { g = rr >> 2; v = rr & 3; }
+        else { g = (rr >> 2) & 1; v = ((rr >> 3) << 2) | (rr & 3); }
+    }
+    static __device__ __forceinline__ int idx_first(int o, int i) {       // i in {0, 1}
+        const int mt = o / TM, mr = o % TM;
+        return (i * TM + mr) * MTS + mt;
+    }
+    static __device__ __forceinline__ int idx_hidden(int o, int i) {
+        const int mt = o / TM, mr = o % TM, t = i / TM;
+        int g, v;
+        split(i % TM, g, v);
+        return ((t * RV + v) * 64 + g * TM + mr) * MTS + mt;
+    }
+    static __device__ __forceinline__ int idx_bias(int o) {
+        int g, v;
+        split(o % TM, g, v);
+        return ((o / TM) * G + g) * RV + v;
+    }
+    static __device__ __forceinline__ int idx_out(int c, int i) {
+        int g, v;
+        split(i % TM, g, v);
+        return (g * KSTEPS + (i / TM) * RV + v) * 4 + c;
+    }
+    // offsets of the segments for a model with L linear layers (L >= 2)
+    static __device__ __host__ __forceinline__ int off_first() { return 0; }
+    static __device__ __host__ __forceinline__ int off_bias(int l) { return FIRST + l * WP; }
+    static __device__ __host__ __forceinline__ int off_hidden(int L, int l) { return FIRST + (L - 1) * WP + (l - 1) * HIDDEN; }
+    static __device__ __host__ __forceinline__ int off_out(int L) { return off_hidden(L, L - 1); }
+    static __device__ __host__ __forceinline__ int off_outb(int L) { return off_out(L) + OUTW; }
+    static __device__ __host__ __forceinline__ int total(int L) { return off_outb(L) + 4; }
+};
+
+// ---- expand + dequantise (Sec. IV-A mask, Sec. IV-B codes) -----------------------------
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+__device__ __forceinline__ uint32_t take_code(const uint32_t *cs, uint32_t rank, uint32_t cb) {
+    const uint32_t bit = rank * cb;
+    const uint32_t w = bit >> 5, sh = bit & 31;
+    const uint64_t two = (uint64_t)cs[w] | ((uint64_t)cs[w + 1] << 32);
+    const uint32_t m = cb == 32 ? 0xFFFFFFFFu : ((1u << cb) - 1u);
+    return (uint32_t)(two >> sh) & m;
+}
+
+// One wavefront rebuilds one layer.  `rec` is the model record (words, in LDS).  put(o, i, w)
+// receives every weight of the true n_out x n_in matrix exactly once (0.0f where pruned);
+// putb(o, b) every bias.
+template <class PutW, class PutB>
+__device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec &r, int lane, PutW put, PutB putb) {
+    const uint32_t n_in = r.n_in, cnt = (uint32_t)r.n_in * r.n_out;
+    const uint32_t nwords = (cnt + 31) >> 5;
+    const uint32_t *mw = rec + (r.mask_off >> 2);
+    const uint32_t *cs = rec + (r.code_off >> 2);
+    const uint32_t cb = r.bits ? r.bits : 32u;
+    uint32_t running = 0;
+    for (uint32_t w0 = 0; w0 < nwords; w0 += 64) {
+        const uint32_t wi = w0 + lane;
+        uint32_t m = 0;
+        if (wi < nwords) {
+            m = r.has_mask ? mw[wi] : 0xFFFFFFFFu;
+            if (!r.has_mask && wi == nwords - 1 && (cnt & 31)) m = (1u << (cnt & 31)) - 1u;
+        }
+        const uint32_t pc = __popc(m);
+        const uint32_t incl = wave_incl_scan(pc, lane);
+        uint32_t rank = incl - pc + running;
+        running += __shfl(incl, 63, 64);
+        if (wi < nwords) {
+            uint32_t k = wi << 5;
+            uint32_t o = k / n_in, i = k - o * n_in;
+            const uint32_t kend = (k + 32 < cnt) ? k + 32 : cnt;
+            for (; k < kend; ++k, m >>= 1) {
+                float val = 0.0f;
+                if (m & 1u) {
+                    const uint32_t code = take_code(cs, rank++, cb);
+                    val = r.bits ? r.scale * (float)((int32_t)code - r.zp) : __uint_as_float(code);
+                }
+                put((int)o, (int)i, val);
+                if (++i == n_in) { i = 0; ++o; }
+            }
+        }
+    }
+    const float *bias = (const float *)(rec + (r.bias_off >> 2));
+    for (uint32_t o = lane; o < r.n_out; o += 64) putb((int)o, bias[o]);
+}
+
+// Whole model: zero the expanded area, then one wavefront per layer.  `pre` scales the
+// weights and biases of the sine layers (w0 / 2pi, so that the pre-activation is in
+// revolutions); the output layer is never scaled.  Ends with a workgroup barrier.
+template <int TM, int WP>
+__device__ __forceinline__ void expand_model(float *lds, const uint32_t *rec, int L, float pre, int tid, int nthreads) {
+    typedef Layout<TM, WP> LY;
+    const int total = LY::total(L);
+    for (int q = tid; q < total; q += nthreads) lds[q] = 0.0f;
+    __syncthreads();
+    const int wave = tid >> 6, lane = tid & 63, nwaves = nthreads >> 6;
+    for (int l = wave; l < L; l += nwaves) {
+        const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
+        if (l == L - 1) {
+            float *w = lds + LY::off_out(L), *b = lds + LY::off_outb(L);
+            expand_layer(rec, r, lane, [=](int o, int i, float v) { w[LY::idx_out(o, i)] = v; },
+                         [=](int o, float v) { b[o] = v; });
+        } else if (l == 0) {
+            float *w = lds + LY::off_first(), *b = lds + LY::off_bias(0);
+            expand_layer(rec, r, lane, [=](int o, int i, float v) { w[LY::idx_first(o, i)] = v * pre; },
+                         [=](int o, float v) { b[LY::idx_bias(o)] = v * pre; });
+        } else {
+            float *w = lds + LY::off_hidden(L, l), *b = lds + LY::off_bias(l);
+            expand_layer(rec, r, lane, [=](int o, int i, float v) { w[LY::idx_hidden(o, i)] = v * pre; },
+                         [=](int o, float v) { b[LY::idx_bias(o)] = v * pre; });
+        }
+    }
+    __syncthreads();
+}
+
+// ---- decode kernel ---------------------------------------------------------------------------
+struct DecodeArgs {
+    const uint8_t *blob;
+    const int64_t *ids;
+    float *out_f32;               // may be NULL
+    uint8_t *out_u8;              // may be NULL
+    unsigned long long *status;   // sticky count of out-of-range ids
+    uint64_t n_models;
+    uint32_t HW, W;
+    float inv2W, inv2H;           // 1/(2W), 1/(2H)
+    float lo, span;               // coordinate = lo + span * (2k+1)/(2n)
+    float pre;                    // w0 / (2 pi)
+    uint32_t chunks;              // workgroups per slot
+    uint32_t tiles_per_chunk;     // 64-pixel tiles per workgroup
+    uint32_t stage_off;           // float offset of the record staging area in LDS
+    uint32_t cls;                 // width class this launch serves (padded width / 16)
+    uint32_t no_clamp;
+    uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
+};
+
+// sin(2 pi r): hardware sine takes its argument in revolutions; fract first keeps the
+// argument in [0, 1) where the instruction is most accurate.
+__device__ __forceinline__ float sin_rev(float r) {
+    return __builtin_amdgcn_sinf(__builtin_amdgcn_fractf(r));
+}
+
+template <int TM, int WP, int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
+    typedef Layout<TM, WP> LY;
+    typedef Tile<TM> T;
+    typedef typename T::acc_t acc_t;
+    constexpr int G = LY::G, RV = LY::RV, MT = LY::MT, MTS = LY::MTS, KSTEPS = LY::KSTEPS;
+    constexpr int NT = G;                      // pixel tiles per wavefront: NT * TM = 64 pixels
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const uint32_t slot = blockIdx.x / a.chunks, chunk = blockIdx.x - slot * a.chunks;
+    const uint32_t tile0 = chunk * a.tiles_per_chunk;
+    const uint32_t ntiles_img = (a.HW + 63) >> 6;
+    if (tile0 >= ntiles_img) return;
+    const uint32_t tile1 = min(tile0 + a.tiles_per_chunk, ntiles_img);
+    const size_t plane0 = (size_t)slot * 3 * a.HW;
+
+    // ---- gather: slot -> id -> index entry (Sec. III-B batch select)
+    const int64_t id = a.ids[slot];
+    if (id < 0 || (uint64_t)id >= a.n_models) {
+        if (!a.handle_bad) return;
+        const uint32_t p0 = tile0 << 6, p1 = min(tile1 << 6, a.HW);
+        for (int c = 0; c < 3; ++c)
+            for (uint32_t p = p0 + tid; p < p1; p += nthreads) {
+                if (a.out_f32) a.out_f32[plane0 + (size_t)c * a.HW + p] = 0.0f;
+                if (a.out_u8) a.out_u8[plane0 + (size_t)c * a.HW + p] = 0;
+            }
+        if (chunk == 0 && tid == 0) atomicAdd(a.status, 1ull);
+        return;
+    }
+    const IndexEntry e = *(const IndexEntry *)(a.blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
+    const uint32_t cls = e.width == 0 ? 1u : (e.width + 15u) >> 4;
+    if (cls != a.cls) return;
+    const int L = e.n_layers;
+
+    // ---- stage the packed record, expand it
+    uint32_t *stage = (uint32_t *)(lds + a.stage_off);
+    {
+        const uint4 *src = (const uint4 *)(a.blob + e.off);
+        uint4 *dst = (uint4 *)stage;
+        for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
+    }
+    expand_model<TM, WP>(lds, stage, L, a.pre, tid, nthreads);   // zero-fill barrier orders the staging too
+
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int g = lane / TM;
+    const float *wfirst = lds + LY::off_first() + lane * MTS;
+    const float *wout = lds + LY::off_out(L) + g * KSTEPS * 4;
+    const float ob0 = lds[LY::off_outb(L) + 0], ob1 = lds[LY::off_outb(L) + 1], ob2 = lds[LY::off_outb(L) + 2];
+
+    for (uint32_t tile = tile0 + wave; tile < tile1; tile += nwaves) {
+        float Bv[NT][KSTEPS];
+        acc_t D[NT][MT];
+        // ---- coordinates of this lane's pixel in each of its NT tiles; lane group 0 feeds x, 1 feeds y
+        float bx[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            uint32_t p = (tile << 6) + nt * TM + (lane % TM);
+            p = min(p, a.HW - 1);
+            const uint32_t row = p / a.W, col = p - row * a.W;
+            const float x = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
+            const float y = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+            bx[nt] = g == 0 ? x : (g == 1 ? y : 0.0f);
+        }
+        // ---- first layer 2 -> width: one k-step, bias as the C operand
+        {
+            float a0[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a0[mt] = wfirst[mt];
+            const float *bt = lds + LY::off_bias(0) + g * RV;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc_t c;
+#pragma unroll
+                for (int v = 0; v < RV; ++v) c[v] = bt[mt * G * RV + v];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(a0[mt], bx[nt], c);
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < RV; ++v) Bv[nt][mt * RV + v] = sin_rev(D[nt][mt][v]);
+        }
+        // ---- hidden layers width -> width
+        for (int l = 1; l < L - 1; ++l) {
+            const float *wl = lds + LY::off_hidden(L, l) + lane * MTS;
+            const float *bt = lds + LY::off_bias(l) + g * RV;
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                float av[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) av[mt] = wl[s * 64 * MTS + mt];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    if (s == 0) {
+                        acc_t c;
+#pragma unroll
+                        for (int v = 0; v < RV; ++v) c[v] = bt[mt * G * RV + v];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(av[mt], Bv[nt][0], c);
+                    } else {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(av[mt], Bv[nt][s], D[nt][mt]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int v = 0; v < RV; ++v) Bv[nt][mt * RV + v] = sin_rev(D[nt][mt][v]);
+        }
+        // ---- output layer width -> 3 on the vector ALU: each lane sums over the rows it owns,
+        //      then the G lane groups are added together
+        float o[NT][3];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) o[nt][0] = o[nt][1] = o[nt][2] = 0.0f;
+#pragma unroll
+        for (int r = 0; r < KSTEPS; ++r) {
+            const f32x4 w4 = *(const f32x4 *)(wout + r * 4);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                o[nt][0] = fmaf(w4[0], Bv[nt][r], o[nt][0]);
+                o[nt][1] = fmaf(w4[1], Bv[nt][r], o[nt][1]);
+                o[nt][2] = fmaf(w4[2], Bv[nt][r], o[nt][2]);
+            }
+        }
+#pragma unroll
+        for (int d = TM; d < 64; d <<= 1)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) o[nt][c] += __shfl_xor(o[nt][c], d, 64);
+        // lane group g stores pixel tile g: lane <-> pixel tile*64 + lane
+        float r0 = o[0][0], r1 = o[0][1], r2 = o[0][2];
+#pragma unroll
+        for (int nt = 1; nt < NT; ++nt)
+            if (g == nt) { r0 = o[nt][0]; r1 = o[nt][1]; r2 = o[nt][2]; }
+        r0 += ob0; r1 += ob1; r2 += ob2;
+        if (!a.no_clamp) {
+            r0 = fminf(fmaxf(r0, 0.0f), 1.0f);
+            r1 = fminf(fmaxf(r1, 0.0f), 1.0f);
+            r2 = fminf(fmaxf(r2, 0.0f), 1.0f);
+        }
+        const uint32_t p = (tile << 6) + lane;
+        if (p < a.HW) {
+            if (a.out_f32) {
+                float *dst = a.out_f32 + plane0 + p;
+                dst[0] = r0; dst[a.HW] = r1; dst[2 * (size_t)a.HW] = r2;
+            }
+            if (a.out_u8) {
+                uint8_t *dst = a.out_u8 + plane0 + p;
+                dst[0] = (uint8_t)rintf(255.0f * r0);
+                dst[a.HW] = (uint8_t)rintf(255.0f * r1);
+                dst[2 * (size_t)a.HW] = (uint8_t)rintf(255.0f * r2);
+            }
+        }
+    }
+}
+
+// ---- debug export of the expand stage -----------------------------------------------------
+template <int TM, int WP>
+__global__ __launch_bounds__(256) void dequant_debug_kernel(const uint8_t *blob, int64_t id, int layer,
+                                                            uint32_t stage_off, float *out, float *bias_out) {
+    typedef Layout<TM, WP> LY;
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const IndexEntry e = *(const IndexEntry *)(blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
+    const int L = e.n_layers;
+    uint32_t *stage = (uint32_t *)(lds + stage_off);
+    {
+        const uint4 *src = (const uint4 *)(blob + e.off);
+        uint4 *dst = (uint4 *)stage;
+        for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
+    }
+    expand_model<TM, WP>(lds, stage, L, 1.0f, tid, nthreads);
+    const LayerRec r = *(const LayerRec *)(stage + layer * (sizeof(LayerRec) / 4));
+    const int n_in = r.n_in, cnt = r.n_in * r.n_out;
+    for (int k = tid; k < cnt; k += nthreads) {
+        const int o = k / n_in, i = k - o * n_in;
+        float v;
+        if (layer == L - 1) v = lds[LY::off_out(L) + LY::idx_out(o, i)];
+        else if (layer == 0) v = lds[LY::off_first() + LY::idx_first(o, i)];
+        else v = lds[LY::off_hidden(L, layer) + LY::idx_hidden(o, i)];
+        out[k] = v;
+    }
+    if (bias_out)
+        for (int o = tid; o < r.n_out; o += nthreads)
+            bias_out[o] = (layer == L - 1) ? lds[LY::off_outb(L) + o] : lds[LY::off_bias(layer) + LY::idx_bias(o)];
+}
+
+}  // namespace rinr
