@@ -132,7 +132,7 @@ def test_gather_exact_with_repeats_and_bad_ids(torch):
             assert not f32[s].any() and not u8[s].any()
     assert st.status() == 4
     st.decode_batch(ids_dev(torch, ids[:100]), H, W)
-    assert st.status() == 6                                  # sticky: 4 + 2 more
+    assert st.status() == 7                                  # sticky: 4 + the 3 bad ids among the first 100
     st.close()
 
 
