@@ -43,6 +43,9 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=0, help="experiment: MFMA tile rows for widths 32/64 (16 or 32)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
+    ap.add_argument("--stagger", type=int, default=-1)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="run only a plain device-to-device copy of MIB MiB per step (counter calibration) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build decodes on one GPU only (images are independent; see DESIGN.md "
@@ -55,6 +58,16 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.copy_calibration:
+        nbytes = args.copy_calibration << 20
+        src = torch.full((nbytes // 4,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": nbytes, "bytes_written": nbytes, "steps": args.steps}))
+        return 0
     rinr.lib()
     if args.tile:
         rinr.tune(0, args.tile)
@@ -62,6 +75,8 @@ def main() -> int:
         rinr.tune(1, args.blocks_per_cu)
     if args.threads:
         rinr.tune(2, args.threads)
+    if args.stagger >= 0:
+        rinr.tune(3, args.stagger)
 
     w = synth.workload(args.config)
     blob = rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)

@@ -162,10 +162,12 @@ int rinr_debug_dequant(const rinr_store *store, int64_t id, int32_t layer, float
 int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
 
 /* Process-wide tuning knobs for experiments; defaults are what the benchmarks use.
- * knob 0: MFMA tile rows for padded widths 32 and 64: 16 (16x16x4 fp32) or 32 (32x32x2 fp32);
- *         read at rinr_store_open.
- * knob 1: grid target in workgroups per compute unit (1..1024).
- * knob 2: threads per workgroup: 0 = by image size, or 256 / 512. */
+ * knob 0: MFMA tile rows for padded widths 32 and 64: 32 (32x32x2 fp32, default) or 16
+ *         (16x16x4 fp32); read at rinr_store_open.
+ * knob 1: 0 = split each slot's pixels over workgroups by the built-in cost model; else a
+ *         fixed grid target in workgroups per compute unit (1..1024).
+ * knob 2: threads per workgroup: 0 = by image size, or 256 / 512.
+ * knob 3: experiment: start delay of some wavefronts (no measurable effect; default 0). */
 int rinr_tune(int knob, int value);
 
 const char *rinr_strerror(int code);

@@ -25,9 +25,10 @@ constexpr uint32_t kLdsLimit = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kThreads = 512;                // launch bound of the decode kernels
 
 // tuning knobs (see rinr_tune)
-int g_tile_rows_wide = 16;      // MFMA tile for classes 2 and 4: 16 (16x16x4) or 32 (32x32x2)
-int g_blocks_per_cu = 8;        // grid target, in workgroups per compute unit
+int g_tile_rows_wide = 32;      // MFMA tile for classes 2 and 4: 16 (16x16x4) or 32 (32x32x2)
+int g_blocks_per_cu = 0;        // 0 = modelled split; else a fixed grid target in workgroups per CU
 int g_threads = 0;              // 0 = choose by image size, else 256 or 512
+int g_stagger = 0;              // start delay of the upper half of the wavefronts, in units of 64 clocks
 
 typedef void (*decode_fn)(const DecodeArgs);
 typedef void (*debug_fn)(const uint8_t *, int64_t, int, uint32_t, float *, float *);
@@ -52,6 +53,42 @@ ClassImpl impl_for(uint32_t cls, int tile_rows_wide) {
     }
 }
 
+// How many workgroups share one slot's pixels.  Every workgroup pays one expand of the model
+// (not overlapped with compute when only one workgroup fits a CU), and the grid runs in rounds
+// of n_cu * resident workgroups, so both very many small workgroups and a last, mostly empty
+// round cost time.  Pick the split that minimises a simple model of both.
+struct Plan { uint32_t chunks, tiles_per_chunk; };
+Plan plan_chunks(double n_slots, uint32_t tiles, uint32_t nw, int n_cu, int resident, double tile_us) {
+    const double expand_us = 15.0;
+    if (n_slots < 1.0) n_slots = 1.0;
+    Plan best{1, ((tiles + nw - 1) / nw) * nw};
+    double best_t = 1e300;
+    if (g_blocks_per_cu > 0) {      // experiment override: fixed target of workgroups per CU
+        uint64_t want = (uint64_t)((double)g_blocks_per_cu * n_cu / n_slots + 0.999);
+        uint32_t max_chunks = tiles / nw ? tiles / nw : 1;
+        uint32_t chunks = (uint32_t)(want < 1 ? 1 : (want > max_chunks ? max_chunks : want));
+        uint32_t tpc = (((tiles + chunks - 1) / chunks + nw - 1) / nw) * nw;
+        return Plan{(tiles + tpc - 1) / tpc, tpc};
+    }
+    uint32_t last_tpc = 0;
+    for (uint32_t c = 1; c <= tiles; ++c) {
+        const uint32_t tpc = (((tiles + c - 1) / c + nw - 1) / nw) * nw;
+        if (tpc == last_tpc) { if (tpc <= nw) break; continue; }
+        last_tpc = tpc;
+        const uint32_t cc = (tiles + tpc - 1) / tpc;
+        const double blocks = n_slots * cc;
+        double r_eff = blocks / n_cu;
+        if (r_eff > resident) r_eff = resident;
+        if (r_eff < 1.0) r_eff = 1.0;
+        const double rounds = std::ceil(blocks / (n_cu * r_eff) - 1e-9);
+        const double round_us = tpc * r_eff / 4.0 * tile_us + (r_eff > 1.5 ? expand_us / r_eff : expand_us);
+        const double t = rounds * round_us;
+        if (t < best_t * 0.995) { best_t = t; best = Plan{cc, tpc}; }
+        if (tpc <= nw) break;
+    }
+    return best;
+}
+
 }  // namespace
 
 struct rinr_store {
@@ -65,14 +102,20 @@ struct rinr_store {
     uint32_t stage_off[kMaxClass + 1];        // floats
     uint32_t lds_bytes[kMaxClass + 1];
     std::vector<IndexEntry> index;            // host copy of the index (debug export, diagnostics)
+    double class_tile_us[kMaxClass + 1];      // modelled time of one 64-pixel tile on one SIMD
+    // launch plan of the last (n, H*W, threads, knob) combination, reused while they repeat
+    mutable int64_t plan_hw;
+    mutable int32_t plan_n, plan_threads, plan_knob;
+    mutable Plan plan[kMaxClass + 1];
     mutable int32_t last_info[4];
 };
 
 extern "C" int rinr_tune(int knob, int value) {
     switch (knob) {
         case 0: if (value != 16 && value != 32) return RINR_E_ARG; g_tile_rows_wide = value; return RINR_OK;
-        case 1: if (value < 1 || value > 1024) return RINR_E_ARG; g_blocks_per_cu = value; return RINR_OK;
+        case 1: if (value < 0 || value > 1024) return RINR_E_ARG; g_blocks_per_cu = value; return RINR_OK;
         case 2: if (value != 0 && value != 256 && value != 512) return RINR_E_ARG; g_threads = value; return RINR_OK;
+        case 3: if (value < 0 || value > 0x3FFFF) return RINR_E_ARG; g_stagger = value; return RINR_OK;
         default: return RINR_E_ARG;
     }
 }
@@ -103,6 +146,20 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         std::memcpy(s->index.data(), (const uint8_t *)host_blob + sizeof(StoreHeader),
                     (size_t)sum.header.n_models * sizeof(IndexEntry));
     std::memset(s->last_info, 0, sizeof s->last_info);
+    s->plan_hw = -1; s->plan_n = -1; s->plan_threads = -1; s->plan_knob = -1;
+    {   // mean matrix work per pixel of each class -> time of a 64-pixel tile on one SIMD's MFMA pipe
+        double macs[kMaxClass + 1] = {0, 0, 0, 0, 0};
+        for (const IndexEntry &e : s->index) {
+            const uint32_t c = e.width == 0 ? 1u : (e.width + 15u) >> 4;
+            const double wp = 16.0 * c;
+            macs[c] += wp * (4.0 + (e.n_layers - 2) * wp);
+        }
+        for (uint32_t c = 1; c <= kMaxClass; ++c) {
+            const double mean = sum.class_count[c] ? macs[c] / (double)sum.class_count[c] : 0.0;
+            // 32 MACs per clock per SIMD at 2.4 GHz, ~87 % of it reachable next to the sine work
+            s->class_tile_us[c] = 64.0 * mean / (32.0 * 2400.0 * 0.87) + 0.5;
+        }
+    }
     for (uint32_t c = 1; c <= kMaxClass; ++c) {
         s->stage_off[c] = s->lds_bytes[c] = 0;
         if (!sum.class_count[c]) continue;
@@ -183,40 +240,47 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     a.span = h.coord_hi - h.coord_lo;
     a.pre = (float)((double)h.w0 / (2.0 * M_PI));
     a.no_clamp = (opts->flags & RINR_FLAG_NO_CLAMP) ? 1u : 0u;
+    a.stagger = (uint32_t)g_stagger;
 
     const uint32_t tiles = (uint32_t)((HW + 63) >> 6);
-    int threads = g_threads ? g_threads : (tiles >= 64 ? 512 : 256);
+    const int threads = g_threads ? g_threads : (tiles >= 64 ? 512 : 256);
     const uint32_t nw = (uint32_t)threads / 64;
-    // workgroups per slot: aim at g_blocks_per_cu * CUs workgroups in total, but never fewer
-    // than one tile per wavefront in a workgroup; tiles per workgroup a multiple of the waves
-    uint64_t want = ((uint64_t)g_blocks_per_cu * (uint64_t)s->n_cu + (uint64_t)n - 1) / (uint64_t)n;
-    uint32_t max_chunks = tiles / nw ? tiles / nw : 1;
-    uint32_t chunks = (uint32_t)(want < 1 ? 1 : (want > max_chunks ? max_chunks : want));
-    uint32_t tpc = (tiles + chunks - 1) / chunks;
-    tpc = ((tpc + nw - 1) / nw) * nw;
-    chunks = (tiles + tpc - 1) / tpc;
-    a.chunks = chunks;
-    a.tiles_per_chunk = tpc;
-    if ((uint64_t)n * chunks > 0x7FFFFFFFull) return RINR_E_SIZE;
 
+    const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads &&
+                          s->plan_knob == g_blocks_per_cu);
     int launches = 0;
     bool first = true;
-    uint32_t big_lds = 0;
+    uint32_t big_lds = 0, total_blocks = 0;
     for (uint32_t c = 1; c <= kMaxClass; ++c) {
         if (!s->sum.class_count[c]) continue;
         const ClassImpl im = impl_for(c, s->tile_rows_wide);
+        if (replan) {
+            int resident = 1;
+            if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)im.decode, threads,
+                                                                      s->lds_bytes[c])) || resident < 1)
+                resident = 1;
+            // expected slots of this class in the batch, if ids are spread like the store's models
+            const double share = (double)s->sum.class_count[c] / (double)(h.n_models ? h.n_models : 1);
+            s->plan[c] = plan_chunks(share * n, tiles, nw, s->n_cu, resident, s->class_tile_us[c]);
+        }
+        const Plan pl = s->plan[c];
+        if ((uint64_t)n * pl.chunks > 0x7FFFFFFFull) return RINR_E_SIZE;
+        a.chunks = pl.chunks;
+        a.tiles_per_chunk = pl.tiles_per_chunk;
         a.cls = c;
         a.stage_off = s->stage_off[c];
         a.handle_bad = first ? 1u : 0u;
         first = false;
-        hipLaunchKernelGGL(im.decode, dim3((uint32_t)n * chunks), dim3((uint32_t)threads), s->lds_bytes[c],
+        hipLaunchKernelGGL(im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), s->lds_bytes[c],
                            (hipStream_t)stream, a);
         RINR_HIP(hipGetLastError());
         ++launches;
+        total_blocks += (uint32_t)n * pl.chunks;
         big_lds = s->lds_bytes[c];
     }
+    s->plan_hw = HW; s->plan_n = n; s->plan_threads = threads; s->plan_knob = g_blocks_per_cu;
     s->last_info[0] = launches;
-    s->last_info[1] = (int32_t)((uint32_t)n * chunks);
+    s->last_info[1] = (int32_t)total_blocks;
     s->last_info[2] = threads;
     s->last_info[3] = (int32_t)big_lds;
     return RINR_OK;

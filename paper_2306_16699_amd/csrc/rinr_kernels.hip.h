@@ -197,6 +197,7 @@ struct DecodeArgs {
     uint32_t cls;                 // width class this launch serves (padded width / 16)
     uint32_t no_clamp;
     uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
+    uint32_t stagger;             // upper half of a workgroup's wavefronts start this many x64 clocks late
 };
 
 // sin(2 pi r): the hardware sine takes its argument in revolutions and reduces the range
@@ -253,6 +254,11 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
 
     const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
     const int g = lane / TM;
+    // Wavefronts w and w + nwaves/2 share a SIMD.  Started together they stay in lock step and
+    // reach their sine / output phases (no MFMA work) at the same time; a one-off delay of one
+    // of them keeps the matrix pipe fed by the other meanwhile.
+    if ((wave >> (a.stagger >> 16)) & 1)
+        for (uint32_t q = 0; q < (a.stagger & 0xFFFF); q += 64) __builtin_amdgcn_s_sleep(64);
     const float *wfirst = lds + LY::off_first() + lane * MTS;
     const float *wout = lds + LY::off_out(L) + g * KSTEPS * 4;
     const float ob0 = lds[LY::off_outb(L) + 0], ob1 = lds[LY::off_outb(L) + 1], ob2 = lds[LY::off_outb(L) + 2];
