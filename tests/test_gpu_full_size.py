@@ -1,0 +1,53 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The whole batch is decoded on the GPU; the oracle checks a seeded sample of slots pixel by
+pixel (plus the first and last slot), and properties that hold at any size are checked on
+everything: range, uint8 = rint(255 * fp32), repeated ids give identical planes.
+"""
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2306_16699_amd import rinr, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+
+
+@pytest.mark.parametrize("k,n_sample", [(1, 64), (2, 512), (3, 96), (4, 32), (5, 32)])
+def test_full_size_workload(k, n_sample):
+    import torch
+    w = synth.workload(k)
+    st = rinr.Store(rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi))
+    ids = torch.from_numpy(w.image_ids).cuda()
+    if w.out_u8:
+        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8)
+        u8 = u8.cpu().numpy()
+    else:
+        f32, u8 = st.decode_batch(ids, w.H, w.W), None
+    raw = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, rinr.FLAG_NO_CLAMP).cpu().numpy()
+    f32 = f32.cpu().numpy()
+    assert st.status() == 0
+    info = st.last_launch_info()
+    assert info["launches"] >= 1 and info["workgroups"] >= 1
+    # properties on the whole batch
+    assert np.isfinite(raw).all()
+    assert f32.min() >= 0.0 and f32.max() <= 1.0
+    assert np.array_equal(f32, np.clip(raw, 0.0, 1.0))
+    if u8 is not None:
+        assert np.array_equal(u8, np.rint(255.0 * f32).astype(np.uint8))
+    order = np.argsort(w.image_ids, kind="stable")
+    same = np.nonzero(np.diff(w.image_ids[order]) == 0)[0]
+    for j in same[:50]:
+        assert np.array_equal(raw[order[j]], raw[order[j + 1]])
+    # oracle on sampled slots
+    rng = np.random.default_rng(100 + k)
+    pick = np.unique(np.concatenate([[0, w.n - 1], rng.choice(w.n, size=min(n_sample, w.n), replace=False)]))
+    ref_raw = oracle.decode(w.models, w.image_ids[pick], w.H, w.W, w.w0, w.coord_lo, w.coord_hi, clamp=False)
+    err = np.abs(raw[pick].astype(np.float64) - ref_raw).max()
+    assert err <= TOL, f"workload {k}: max-abs {err}"
+    if u8 is not None:
+        ref8 = np.rint(255.0 * np.clip(ref_raw, 0.0, 1.0)).astype(np.int32)
+        assert np.abs(u8[pick].astype(np.int32) - ref8).max() <= 1
+    print(f"workload {k}: {len(pick)} slots checked, max-abs {err:.2e}, launch {info}")
+    st.close()
