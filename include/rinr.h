@@ -118,7 +118,10 @@ int rinr_store_info(const rinr_store *store, int64_t *n_models, int32_t *max_wid
 enum { RINR_OUT_F32 = 1,           /* out: float [n][3][H][W], clamp(y, 0, 1)                 */
        RINR_OUT_U8 = 2,            /* out: uint8 [n][3][H][W], rint(255 * clamp(y, 0, 1))     */
        RINR_OUT_F32_AND_U8 = 3 };  /* out: float tensor, opts.out_u8: uint8 tensor            */
-enum { RINR_FLAG_NO_CLAMP = 1 };   /* fp32 output only: write the linear output unclamped     */
+enum { RINR_FLAG_NO_CLAMP = 1,     /* fp32 output only: write the linear output unclamped     */
+       RINR_FLAG_FP32_MFMA = 2 };  /* run the layers on fp32 MFMA instead of the default
+                                      split-precision fp16 MFMA (hi+lo operand pairs, fp32
+                                      accumulate); same results within the stated tolerance  */
 
 typedef struct {
     int32_t out_dtype;       /* RINR_OUT_*                                              */
@@ -167,7 +170,8 @@ int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
  * knob 1: 0 = split each slot's pixels over workgroups by the built-in cost model; else a
  *         fixed grid target in workgroups per compute unit (1..1024).
  * knob 2: threads per workgroup: 0 = by image size, or 256 / 512.
- * knob 3: experiment: start delay of some wavefronts (no measurable effect; default 0). */
+ * knob 3: experiment: start delay of some wavefronts (default 0).
+ * knob 4: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA). */
 int rinr_tune(int knob, int value);
 
 const char *rinr_strerror(int code);

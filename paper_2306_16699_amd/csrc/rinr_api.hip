@@ -1,8 +1,10 @@
 // GPU side of the C ABI: store handle, launch logic for the decode kernels.
 #include "../../include/rinr.h"
 #include "rinr_kernels.hip.h"
+#include "rinr_xdl.hip.h"
 #include "rinr_validate.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -28,20 +30,23 @@ constexpr int kThreads = 512;                // launch bound of the decode kerne
 int g_tile_rows_wide = 32;      // MFMA tile for classes 2 and 4: 16 (16x16x4) or 32 (32x32x2)
 int g_blocks_per_cu = 0;        // 0 = modelled split; else a fixed grid target in workgroups per CU
 int g_threads = 0;              // 0 = choose by image size, else 256 or 512
+int g_force_fp32 = 0;           // 1 = always use the fp32 MFMA kernel
 int g_stagger = 0;              // start delay of the upper half of the wavefronts, in units of 64 clocks
 
 typedef void (*decode_fn)(const DecodeArgs);
 typedef void (*debug_fn)(const uint8_t *, int64_t, int, uint32_t, float *, float *);
 
 struct ClassImpl {
-    decode_fn decode;
+    decode_fn decode;      // fp32 MFMA kernel
+    decode_fn decode_xdl;  // split-precision fp16 MFMA kernel
     debug_fn debug;
-    int (*total)(int L);   // expanded floats for L layers
+    int (*total)(int L);   // expanded floats for L layers (fp32 kernel)
 };
 
 template <int TM, int WP> int total_of(int L) { return Layout<TM, WP>::total(L); }
 template <int TM, int WP> ClassImpl make_impl() {
-    return ClassImpl{decode_kernel<TM, WP, kThreads>, dequant_debug_kernel<TM, WP>, total_of<TM, WP>};
+    return ClassImpl{decode_kernel<TM, WP, kThreads>, decode_xdl_kernel<WP / 16, kThreads>, dequant_debug_kernel<TM, WP>,
+                     total_of<TM, WP>};
 }
 
 ClassImpl impl_for(uint32_t cls, int tile_rows_wide) {
@@ -103,6 +108,10 @@ struct rinr_store {
     uint32_t lds_bytes[kMaxClass + 1];
     std::vector<IndexEntry> index;            // host copy of the index (debug export, diagnostics)
     double class_tile_us[kMaxClass + 1];      // modelled time of one 64-pixel tile on one SIMD
+    double class_tile_us_xdl[kMaxClass + 1];
+    bool xdl_ok;                              // every weight fits fp16 range after pre-scaling
+    uint32_t xdl_stage_off[kMaxClass + 1];    // floats
+    uint32_t xdl_lds_bytes[kMaxClass + 1];
     // launch plan of the last (n, H*W, threads, knob) combination, reused while they repeat
     mutable int64_t plan_hw;
     mutable int32_t plan_n, plan_threads, plan_knob;
@@ -115,6 +124,7 @@ extern "C" int rinr_tune(int knob, int value) {
         case 0: if (value != 16 && value != 32) return RINR_E_ARG; g_tile_rows_wide = value; return RINR_OK;
         case 1: if (value < 0 || value > 1024) return RINR_E_ARG; g_blocks_per_cu = value; return RINR_OK;
         case 2: if (value != 0 && value != 256 && value != 512) return RINR_E_ARG; g_threads = value; return RINR_OK;
+        case 4: if (value != 0 && value != 1) return RINR_E_ARG; g_force_fp32 = value; return RINR_OK;
         case 3: if (value < 0 || value > 0x3FFFF) return RINR_E_ARG; g_stagger = value; return RINR_OK;
         default: return RINR_E_ARG;
     }
@@ -160,6 +170,45 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
             s->class_tile_us[c] = 64.0 * mean / (32.0 * 2400.0 * 0.87) + 0.5;
         }
     }
+    {   // split-precision kernel: LDS need per class and fp16 range of every operand it would build
+        const uint8_t *hb = (const uint8_t *)host_blob;
+        const float pre = (float)((double)sum.header.w0 / (2.0 * M_PI));
+        uint32_t need[kMaxClass + 1] = {0, 0, 0, 0, 0};
+        double acts[kMaxClass + 1] = {0, 0, 0, 0, 0};
+        s->xdl_ok = true;
+        for (const IndexEntry &e : s->index) {
+            const uint32_t c = e.width == 0 ? 1u : (e.width + 15u) >> 4;
+            int n_int = 0, n_raw = 0;
+            for (int l = 0; l < e.n_layers; ++l) {
+                LayerRec r;
+                std::memcpy(&r, hb + e.off + (size_t)l * sizeof(LayerRec), sizeof r);
+                const bool hidden = l > 0 && l < e.n_layers - 1;
+                const float k = l < e.n_layers - 1 ? pre : 1.0f;
+                if (hidden && xdl_int_layer(r.bits, r.scale * pre)) { ++n_int; continue; }
+                if (hidden) ++n_raw;
+                float wmax = 0.0f;
+                if (r.bits == 0) {
+                    const float *w = (const float *)(hb + e.off + r.code_off);
+                    for (uint32_t q = 0; q < r.n_kept; ++q) wmax = std::fmax(wmax, std::fabs(w[q]));
+                } else {
+                    const float span = (float)std::max<int64_t>(r.zp, ((int64_t)1 << r.bits) - 1 - r.zp);
+                    wmax = std::fabs(r.scale) * span;
+                }
+                if (!(wmax * std::fabs(k) < 60000.0f)) s->xdl_ok = false;
+            }
+            const uint32_t b = xdl_model_bytes((int)c, e.n_layers, n_int, n_raw);
+            if (b > need[c]) need[c] = b;
+            acts[c] += (e.n_layers - 1) * 16.0 * c;
+        }
+        for (uint32_t c = 1; c <= kMaxClass; ++c) {
+            s->xdl_stage_off[c] = need[c] / 4;
+            s->xdl_lds_bytes[c] = need[c] + sum.class_max_bytes[c];
+            if (sum.class_count[c] && s->xdl_lds_bytes[c] > kLdsLimit) s->xdl_ok = false;
+            // vector-ALU bound: ~20 clocks per activation per lane (sine + hi/lo split), 64 lanes = 64 pixels
+            const double mean = sum.class_count[c] ? acts[c] / (double)sum.class_count[c] : 0.0;
+            s->class_tile_us_xdl[c] = (mean * 20.0 + 600.0) / 2400.0;
+        }
+    }
     for (uint32_t c = 1; c <= kMaxClass; ++c) {
         s->stage_off[c] = s->lds_bytes[c] = 0;
         if (!sum.class_count[c]) continue;
@@ -171,6 +220,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         s->stage_off[c] = tot;
         s->lds_bytes[c] = (uint32_t)need;
         if (hip_fail(hipFuncSetAttribute((const void *)im.decode, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+            hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
             hip_fail(hipFuncSetAttribute((const void *)im.debug, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
             delete s;
             return RINR_E_HIP;
@@ -212,7 +262,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (n < 0 || H <= 0 || W <= 0) return RINR_E_ARG;
     const int dt = opts->out_dtype;
     if (dt != RINR_OUT_F32 && dt != RINR_OUT_U8 && dt != RINR_OUT_F32_AND_U8) return RINR_E_ARG;
-    if (opts->flags & ~RINR_FLAG_NO_CLAMP) return RINR_E_ARG;
+    if (opts->flags & ~(RINR_FLAG_NO_CLAMP | RINR_FLAG_FP32_MFMA)) return RINR_E_ARG;
     if ((opts->flags & RINR_FLAG_NO_CLAMP) && dt != RINR_OUT_F32) return RINR_E_ARG;
     const int64_t HW = (int64_t)H * W;
     if (HW >= (int64_t)1 << 31) return RINR_E_SIZE;
@@ -241,13 +291,15 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     a.pre = (float)((double)h.w0 / (2.0 * M_PI));
     a.no_clamp = (opts->flags & RINR_FLAG_NO_CLAMP) ? 1u : 0u;
     a.stagger = (uint32_t)g_stagger;
+    a.neg1 = -1.0f;
+    const bool xdl = s->xdl_ok && !(opts->flags & RINR_FLAG_FP32_MFMA) && !g_force_fp32;
 
     const uint32_t tiles = (uint32_t)((HW + 63) >> 6);
     const int threads = g_threads ? g_threads : (tiles >= 64 ? 512 : 256);
     const uint32_t nw = (uint32_t)threads / 64;
 
-    const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads &&
-                          s->plan_knob == g_blocks_per_cu);
+    const int knob = g_blocks_per_cu * 2 + (xdl ? 1 : 0);
+    const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads && s->plan_knob == knob);
     int launches = 0;
     bool first = true;
     uint32_t big_lds = 0, total_blocks = 0;
@@ -256,29 +308,31 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
         const ClassImpl im = impl_for(c, s->tile_rows_wide);
         if (replan) {
             int resident = 1;
-            if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)im.decode, threads,
-                                                                      s->lds_bytes[c])) || resident < 1)
+            if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)(xdl ? im.decode_xdl : im.decode),
+                                                                      threads, xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c])) ||
+                resident < 1)
                 resident = 1;
             // expected slots of this class in the batch, if ids are spread like the store's models
             const double share = (double)s->sum.class_count[c] / (double)(h.n_models ? h.n_models : 1);
-            s->plan[c] = plan_chunks(share * n, tiles, nw, s->n_cu, resident, s->class_tile_us[c]);
+            s->plan[c] = plan_chunks(share * n, tiles, nw, s->n_cu, resident, xdl ? s->class_tile_us_xdl[c] : s->class_tile_us[c]);
         }
         const Plan pl = s->plan[c];
         if ((uint64_t)n * pl.chunks > 0x7FFFFFFFull) return RINR_E_SIZE;
         a.chunks = pl.chunks;
         a.tiles_per_chunk = pl.tiles_per_chunk;
         a.cls = c;
-        a.stage_off = s->stage_off[c];
+        a.stage_off = xdl ? s->xdl_stage_off[c] : s->stage_off[c];
         a.handle_bad = first ? 1u : 0u;
         first = false;
-        hipLaunchKernelGGL(im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), s->lds_bytes[c],
+        const uint32_t lds_bytes = xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c];
+        hipLaunchKernelGGL(xdl ? im.decode_xdl : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
                            (hipStream_t)stream, a);
         RINR_HIP(hipGetLastError());
         ++launches;
         total_blocks += (uint32_t)n * pl.chunks;
-        big_lds = s->lds_bytes[c];
+        big_lds = lds_bytes;
     }
-    s->plan_hw = HW; s->plan_n = n; s->plan_threads = threads; s->plan_knob = g_blocks_per_cu;
+    s->plan_hw = HW; s->plan_n = n; s->plan_threads = threads; s->plan_knob = knob;
     s->last_info[0] = launches;
     s->last_info[1] = (int32_t)total_blocks;
     s->last_info[2] = threads;

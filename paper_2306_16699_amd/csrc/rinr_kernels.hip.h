@@ -109,9 +109,10 @@ __device__ __forceinline__ uint32_t take_code(const uint32_t *cs, uint32_t rank,
     return (uint32_t)(two >> sh) & m;
 }
 
-// One wavefront rebuilds one layer.  `rec` is the model record (words, in LDS).  put(o, i, w)
-// receives every weight of the true n_out x n_in matrix exactly once (0.0f where pruned);
-// putb(o, b) every bias.
+// One wavefront rebuilds one layer.  `rec` is the model record (words, in LDS).  put(o, i, w, q)
+// receives every weight of the true n_out x n_in matrix exactly once: w the fp32 value (0.0f
+// where pruned) and q the integer code - zp of a coded layer (0 where pruned or for fp32
+// layers); putb(o, b) every bias.
 template <class PutW, class PutB>
 __device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec &r, int lane, PutW put, PutB putb) {
     const uint32_t n_in = r.n_in, cnt = (uint32_t)r.n_in * r.n_out;
@@ -137,11 +138,13 @@ __device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec
             const uint32_t kend = (k + 32 < cnt) ? k + 32 : cnt;
             for (; k < kend; ++k, m >>= 1) {
                 float val = 0.0f;
+                int32_t q = 0;
                 if (m & 1u) {
                     const uint32_t code = take_code(cs, rank++, cb);
-                    val = r.bits ? r.scale * (float)((int32_t)code - r.zp) : __uint_as_float(code);
+                    if (r.bits) { q = (int32_t)code - r.zp; val = r.scale * (float)q; }
+                    else val = __uint_as_float(code);
                 }
-                put((int)o, (int)i, val);
+                put((int)o, (int)i, val, q);
                 if (++i == n_in) { i = 0; ++o; }
             }
         }
@@ -164,15 +167,15 @@ __device__ __forceinline__ void expand_model(float *lds, const uint32_t *rec, in
         const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
         if (l == L - 1) {
             float *w = lds + LY::off_out(L), *b = lds + LY::off_outb(L);
-            expand_layer(rec, r, lane, [=](int o, int i, float v) { w[LY::idx_out(o, i)] = v; },
+            expand_layer(rec, r, lane, [=](int o, int i, float v, int) { w[LY::idx_out(o, i)] = v; },
                          [=](int o, float v) { b[o] = v; });
         } else if (l == 0) {
             float *w = lds + LY::off_first(), *b = lds + LY::off_bias(0);
-            expand_layer(rec, r, lane, [=](int o, int i, float v) { w[LY::idx_first(o, i)] = v * pre; },
+            expand_layer(rec, r, lane, [=](int o, int i, float v, int) { w[LY::idx_first(o, i)] = v * pre; },
                          [=](int o, float v) { b[LY::idx_bias(o)] = v * pre; });
         } else {
             float *w = lds + LY::off_hidden(L, l), *b = lds + LY::off_bias(l);
-            expand_layer(rec, r, lane, [=](int o, int i, float v) { w[LY::idx_hidden(o, i)] = v * pre; },
+            expand_layer(rec, r, lane, [=](int o, int i, float v, int) { w[LY::idx_hidden(o, i)] = v * pre; },
                          [=](int o, float v) { b[LY::idx_bias(o)] = v * pre; });
         }
     }
@@ -197,7 +200,8 @@ struct DecodeArgs {
     uint32_t cls;                 // width class this launch serves (padded width / 16)
     uint32_t no_clamp;
     uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
-    uint32_t stagger;             // upper half of a workgroup's wavefronts start this many x64 clocks late
+    uint32_t stagger;             // experiment: start delay of some wavefronts, in units of 64 clocks
+    float neg1;                   // -1.0f, passed as data (keeps a subtraction in mixed-precision fma form)
 };
 
 // sin(2 pi r): the hardware sine takes its argument in revolutions and reduces the range

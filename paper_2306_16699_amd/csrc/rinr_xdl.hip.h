@@ -1,0 +1,358 @@
+// Split-precision decode kernel: the layers' contractions run on the fp16 matrix cores
+// (v_mfma_f32_16x16x32_f16 / 16x16x16_f16, fp32 accumulate) with every fp32 operand carried
+// as an exact-sum pair of halfs, hi = fp16(x), lo = fp16(x - hi), so a product keeps ~22
+// significant bits:  W*h ~= Wh*hh + Wh*hl + Wl*hh   (the dropped Wl*hl is 2^-22 relative).
+// A hidden layer stored as 2..8-bit codes (Sec. IV-B) needs no low part at all: its integers
+// q - zp are exact in fp16, so W*h = scale * (Q*hh + Q*hl) and the scale moves into the sine
+// epilogue.  Unlike fp32 MFMA, the fp16 matrix pipe runs concurrently with the vector ALU on
+// this chip, so the sine + split work of one wavefront hides behind the matrix work of
+// another; the method and its results (Sec. III-B decode) are unchanged.
+//
+// Same structure as the fp32 kernel: workgroup = (slot, range of 64-pixel tiles), model
+// expanded once into LDS, activations register-resident across layers.  Tile = 16 rows x 16
+// pixels, lane = (n = lane % 16, g = lane / 16); accumulator register v of a lane holds row
+// 4g + v of its tile.  A 32-deep k-step takes from lane group g the 8 activations that group
+// holds of two consecutive row tiles (2j, 2j+1), so again nothing crosses lanes.
+#pragma once
+#include "rinr_kernels.hip.h"
+
+namespace rinr {
+
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+typedef _Float16 h4v __attribute__((ext_vector_type(4)));
+typedef _Float16 h8v __attribute__((ext_vector_type(8)));
+typedef float f2v __attribute__((ext_vector_type(2)));
+
+// A hidden layer takes the two-term integer form when its codes are exact in fp16 and the
+// scale is a usable multiplier; otherwise its dequantised fp32 weights are split hi/lo.
+__host__ __device__ inline bool xdl_int_layer(uint32_t bits, float scale_pre) {
+    const float a = scale_pre < 0 ? -scale_pre : scale_pre;
+    return bits >= 2 && bits <= 8 && a >= 1e-30f && a <= 1e30f;
+}
+
+struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
+    uint32_t off_hi;       // byte offset of the fp16 operand block
+    uint32_t off_lo;       // byte offset of the low-part block, 0 = none (integer layer)
+    float scale;           // multiplies the accumulator before the sine (1 unless integer layer)
+    uint32_t off_bias;     // byte offset of the fp32 bias tile(s)
+};
+
+template <int MT> struct XLayout {
+    static constexpr int WP = 16 * MT;
+    static constexpr int KJ = MT / 2;              // 32-deep k-steps of a hidden layer
+    static constexpr int K16 = MT % 2;             // plus one 16-deep step for an odd last tile
+    static constexpr int TABLE = 16 * 16;          // bytes: one XLayer per linear layer, 16 at most
+    static constexpr int HID = 256 * MT * MT * 2;  // bytes of one hidden operand block
+    static constexpr int FIRST = MT * 64 * 16;     // bytes: [mt][lane][8 halfs], hi and lo in one k-step
+    static constexpr int OUT = (KJ * 64 * 16 + K16 * 64 * 8);   // bytes: one 16-row tile
+    // half index of hidden weight (o, i) inside its block
+    static __device__ __forceinline__ int idx_hidden(int o, int i) {
+        const int mt = o >> 4, m = o & 15, t = i >> 4, g = (i >> 2) & 3, v = i & 3;
+        if (t < 2 * KJ) return (((t >> 1) * MT + mt) * 64 + g * 16 + m) * 8 + (t & 1) * 4 + v;
+        return KJ * MT * 512 + (mt * 64 + g * 16 + m) * 4 + v;
+    }
+    static __device__ __forceinline__ int idx_first(int o, int e) { return ((o >> 4) * 64 + (o & 15)) * 8 + e; }
+    // output channel c sits in row 4c of the single output tile, i.e. lane group c, register 0
+    static __device__ __forceinline__ int idx_out(int c, int i) {
+        const int t = i >> 4, g = (i >> 2) & 3, v = i & 3, lane = g * 16 + 4 * c;
+        if (t < 2 * KJ) return ((t >> 1) * 64 + lane) * 8 + (t & 1) * 4 + v;
+        return KJ * 512 + lane * 4 + v;
+    }
+    static __device__ __forceinline__ int idx_bias(int o) { return ((o >> 4) * 4 + ((o >> 2) & 3)) * 4 + (o & 3); }
+};
+
+// Bytes of LDS the expanded model needs (without the staging copy of the record).
+// n_int = hidden layers in integer form, n_raw = hidden layers split hi/lo.
+__host__ __device__ inline uint32_t xdl_model_bytes(int mt, int n_layers, int n_int, int n_raw) {
+    const uint32_t wp = 16u * mt, hid = 512u * mt * mt;
+    const uint32_t out = (uint32_t)((mt / 2) * 1024 + (mt % 2) * 512);
+    return 16u * 16u + ((uint32_t)(n_layers - 1) * wp + 16u) * 4u + (uint32_t)mt * 1024u +
+           hid * (uint32_t)(n_int + 2 * n_raw) + 2u * out;
+}
+
+template <int MT>
+__device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec, int L, float pre, int tid, int nthreads,
+                                                 uint32_t total_bytes) {
+    typedef XLayout<MT> LY;
+    XLayer *tab = (XLayer *)lds;
+    for (uint32_t q = tid; q < (total_bytes >> 2); q += nthreads) ((uint32_t *)lds)[q] = 0u;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t bias = LY::TABLE;
+        uint32_t cur = LY::TABLE + ((uint32_t)(L - 1) * LY::WP + 16u) * 4u;
+        for (int l = 0; l < L; ++l) {
+            const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
+            XLayer e;
+            e.off_bias = bias;
+            bias += (l < L - 1 ? LY::WP : 16) * 4;
+            e.scale = 1.0f;
+            e.off_hi = cur;
+            e.off_lo = 0;
+            if (l == 0) cur += LY::FIRST;
+            else if (l == L - 1) { e.off_lo = cur + LY::OUT; cur += 2 * LY::OUT; }
+            else if (xdl_int_layer(r.bits, r.scale * pre)) { e.scale = r.scale * pre; cur += LY::HID; }
+            else { e.off_lo = cur + LY::HID; cur += 2 * LY::HID; }
+            tab[l] = e;
+        }
+    }
+    __syncthreads();
+    const int wave = tid >> 6, lane = tid & 63, nwaves = nthreads >> 6;
+    for (int l = wave; l < L; l += nwaves) {
+        const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
+        const XLayer e = tab[l];
+        _Float16 *hi = (_Float16 *)(lds + e.off_hi), *lo = (_Float16 *)(lds + e.off_lo);
+        float *bt = (float *)(lds + e.off_bias);
+        if (l == L - 1) {
+            expand_layer(rec, r, lane,
+                         [=](int o, int i, float v, int) {
+                             const _Float16 h = (_Float16)v;
+                             hi[LY::idx_out(o, i)] = h;
+                             lo[LY::idx_out(o, i)] = (_Float16)(v - (float)h);
+                         },
+                         [=](int o, float v) { bt[o * 4] = v; });
+        } else if (l == 0) {
+            expand_layer(rec, r, lane,
+                         [=](int o, int i, float v, int) {
+                             const float w = v * pre;
+                             const _Float16 h = (_Float16)w, lw = (_Float16)(w - (float)h);
+                             hi[LY::idx_first(o, i)] = h;          // pairs with the coordinate's high half
+                             hi[LY::idx_first(o, 2 + i)] = h;      // ... with its low half
+                             hi[LY::idx_first(o, 4 + i)] = lw;     // low weight part x high coordinate half
+                         },
+                         [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre; });
+        } else if (e.off_lo == 0) {
+            const float inv = 1.0f / e.scale;
+            expand_layer(rec, r, lane, [=](int o, int i, float, int q) { hi[LY::idx_hidden(o, i)] = (_Float16)(float)q; },
+                         [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre * inv; });
+        } else {
+            expand_layer(rec, r, lane,
+                         [=](int o, int i, float v, int) {
+                             const float w = v * pre;
+                             const _Float16 h = (_Float16)w;
+                             hi[LY::idx_hidden(o, i)] = h;
+                             lo[LY::idx_hidden(o, i)] = (_Float16)(w - (float)h);
+                         },
+                         [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre; });
+        }
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ f32x4 mfma32h(h8v a, h8v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+__device__ __forceinline__ f32x4 mfma16h(h4v a, h4v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
+
+// sine of the four accumulator values of one tile, then the exact hi/lo split of the results.
+// neg1 is -1.0f passed as data so that h - float(hi) stays a single mixed-precision fma.
+__device__ __forceinline__ void sine_split(const f32x4 d, float scale, float neg1, h4v &hi, h4v &lo) {
+    const f2v p0 = {sin_rev(d[0] * scale), sin_rev(d[1] * scale)};
+    const f2v p1 = {sin_rev(d[2] * scale), sin_rev(d[3] * scale)};
+    const h2v a0 = __builtin_convertvector(p0, h2v), a1 = __builtin_convertvector(p1, h2v);
+    const f2v r0 = {__builtin_fmaf((float)a0[0], neg1, p0[0]), __builtin_fmaf((float)a0[1], neg1, p0[1])};
+    const f2v r1 = {__builtin_fmaf((float)a1[0], neg1, p1[0]), __builtin_fmaf((float)a1[1], neg1, p1[1])};
+    const h2v b0 = __builtin_convertvector(r0, h2v), b1 = __builtin_convertvector(r1, h2v);
+    hi = (h4v){a0[0], a0[1], a1[0], a1[1]};
+    lo = (h4v){b0[0], b0[1], b1[0], b1[1]};
+}
+
+template <int MT, int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a) {
+    typedef XLayout<MT> LY;
+    constexpr int KJ = LY::KJ, K16 = LY::K16, NT = 4;
+    constexpr int KJA = KJ ? KJ : 1;           // array extents must not be zero
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    char *lds = (char *)lds_f;
+
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const uint32_t slot = blockIdx.x / a.chunks, chunk = blockIdx.x - slot * a.chunks;
+    const uint32_t tile0 = chunk * a.tiles_per_chunk;
+    const uint32_t ntiles_img = (a.HW + 63) >> 6;
+    if (tile0 >= ntiles_img) return;
+    const uint32_t tile1 = min(tile0 + a.tiles_per_chunk, ntiles_img);
+    const size_t plane0 = (size_t)slot * 3 * a.HW;
+
+    const int64_t id = a.ids[slot];
+    if (id < 0 || (uint64_t)id >= a.n_models) {
+        if (!a.handle_bad) return;
+        const uint32_t p0 = tile0 << 6, p1 = min(tile1 << 6, a.HW);
+        for (int c = 0; c < 3; ++c)
+            for (uint32_t p = p0 + tid; p < p1; p += nthreads) {
+                if (a.out_f32) a.out_f32[plane0 + (size_t)c * a.HW + p] = 0.0f;
+                if (a.out_u8) a.out_u8[plane0 + (size_t)c * a.HW + p] = 0;
+            }
+        if (chunk == 0 && tid == 0) atomicAdd(a.status, 1ull);
+        return;
+    }
+    const IndexEntry e = *(const IndexEntry *)(a.blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
+    const uint32_t cls = e.width == 0 ? 1u : (e.width + 15u) >> 4;
+    if (cls != a.cls) return;
+    const int L = e.n_layers;
+
+    uint32_t *stage = (uint32_t *)(lds_f + a.stage_off);
+    {
+        const uint4 *src = (const uint4 *)(a.blob + e.off);
+        uint4 *dst = (uint4 *)stage;
+        for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
+    }
+    xdl_expand_model<MT>(lds, stage, L, a.pre, tid, nthreads, a.stage_off << 2);
+
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int g = lane >> 4, n = lane & 15;
+    if ((wave >> (a.stagger >> 16)) & 1)
+        for (uint32_t q = 0; q < (a.stagger & 0xFFFF); q += 64) __builtin_amdgcn_s_sleep(64);
+    const XLayer *tab = (const XLayer *)lds;
+    const float neg1 = a.neg1;
+
+    for (uint32_t tile = tile0 + wave; tile < tile1; tile += nwaves) {
+        h8v Hh[NT][KJA], Hl[NT][KJA];
+        h4v Hh4[NT], Hl4[NT];
+        f32x4 D[NT][MT];
+        // ---- first layer: coordinates as hi/lo halfs in lane group 0; k slots (xh, yh, xl, yl, xh, yh, 0, 0)
+        {
+            const XLayer e0 = tab[0];
+            const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
+            const f32x4 *bt = (const f32x4 *)(lds + e0.off_bias) + g;
+            h8v b0[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                uint32_t p = (tile << 6) + nt * 16 + n;
+                p = min(p, a.HW - 1);
+                const uint32_t row = p / a.W, col = p - row * a.W;
+                const float x = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
+                const float y = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+                const _Float16 xh = (_Float16)x, yh = (_Float16)y;
+                const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
+                const _Float16 z = (_Float16)0.0f;
+                b0[nt] = g == 0 ? (h8v){xh, yh, xl, yl, xh, yh, z, z} : (h8v){z, z, z, z, z, z, z, z};
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const h8v av = a0[mt * 64];
+                const f32x4 c = bt[mt * 4];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) D[nt][mt] = mfma32h(av, b0[nt], c);
+            }
+        }
+        float scale = 1.0f;
+        for (int l = 1; l < L; ++l) {
+            // ---- sine + split of layer l-1's accumulators -> operands of layer l
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    h4v hi, lo;
+                    sine_split(D[nt][t], scale, neg1, hi, lo);
+                    if (t < 2 * KJ) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) { Hh[nt][t >> 1][(t & 1) * 4 + v] = hi[v]; Hl[nt][t >> 1][(t & 1) * 4 + v] = lo[v]; }
+                    } else { Hh4[nt] = hi; Hl4[nt] = lo; }
+                }
+            if (l == L - 1) break;
+            // ---- hidden layer l
+            const XLayer el = tab[l];
+            scale = el.scale;
+            const h8v *ah = (const h8v *)(lds + el.off_hi) + lane;
+            const h8v *al = (const h8v *)(lds + el.off_lo) + lane;
+            const h4v *ah4 = (const h4v *)(lds + el.off_hi + KJ * MT * 1024) + lane;
+            const h4v *al4 = (const h4v *)(lds + el.off_lo + KJ * MT * 1024) + lane;
+            const f32x4 *bt = (const f32x4 *)(lds + el.off_bias) + g;
+            const bool has_lo = el.off_lo != 0;
+            if (!has_lo) {
+#pragma unroll
+                for (int j = 0; j < KJ; ++j)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const h8v av = ah[(j * MT + mt) * 64];
+                        const f32x4 c = bt[mt * 4];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            D[nt][mt] = mfma32h(av, Hh[nt][j], j == 0 ? c : D[nt][mt]);
+                            D[nt][mt] = mfma32h(av, Hl[nt][j], D[nt][mt]);
+                        }
+                    }
+                if (K16) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const h4v av = ah4[mt * 64];
+                        const f32x4 c = bt[mt * 4];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            D[nt][mt] = mfma16h(av, Hh4[nt], KJ == 0 ? c : D[nt][mt]);
+                            D[nt][mt] = mfma16h(av, Hl4[nt], D[nt][mt]);
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < KJ; ++j)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const h8v av = ah[(j * MT + mt) * 64], aw = al[(j * MT + mt) * 64];
+                        const f32x4 c = bt[mt * 4];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            D[nt][mt] = mfma32h(av, Hh[nt][j], j == 0 ? c : D[nt][mt]);
+                            D[nt][mt] = mfma32h(av, Hl[nt][j], D[nt][mt]);
+                            D[nt][mt] = mfma32h(aw, Hh[nt][j], D[nt][mt]);
+                        }
+                    }
+                if (K16) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const h4v av = ah4[mt * 64], aw = al4[mt * 64];
+                        const f32x4 c = bt[mt * 4];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            D[nt][mt] = mfma16h(av, Hh4[nt], KJ == 0 ? c : D[nt][mt]);
+                            D[nt][mt] = mfma16h(av, Hl4[nt], D[nt][mt]);
+                            D[nt][mt] = mfma16h(aw, Hh4[nt], D[nt][mt]);
+                        }
+                    }
+                }
+            }
+        }
+        // ---- output layer width -> 3: one 16-row tile, channel c in row 4c = lane group c, register 0
+        {
+            const XLayer eo = tab[L - 1];
+            const h8v *ah = (const h8v *)(lds + eo.off_hi) + lane;
+            const h8v *al = (const h8v *)(lds + eo.off_lo) + lane;
+            const h4v *ah4 = (const h4v *)(lds + eo.off_hi + KJ * 1024) + lane;
+            const h4v *al4 = (const h4v *)(lds + eo.off_lo + KJ * 1024) + lane;
+            const f32x4 c = ((const f32x4 *)(lds + eo.off_bias))[g];
+            f32x4 O[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) O[nt] = c;
+#pragma unroll
+            for (int j = 0; j < KJ; ++j) {
+                const h8v av = ah[j * 64], aw = al[j * 64];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    O[nt] = mfma32h(av, Hh[nt][j], O[nt]);
+                    O[nt] = mfma32h(av, Hl[nt][j], O[nt]);
+                    O[nt] = mfma32h(aw, Hh[nt][j], O[nt]);
+                }
+            }
+            if (K16) {
+                const h4v av = ah4[0], aw = al4[0];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    O[nt] = mfma16h(av, Hh4[nt], O[nt]);
+                    O[nt] = mfma16h(av, Hl4[nt], O[nt]);
+                    O[nt] = mfma16h(aw, Hh4[nt], O[nt]);
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float r = O[nt][0];
+                if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
+                const uint32_t p = (tile << 6) + nt * 16 + n;
+                if (g < 3 && p < a.HW) {
+                    const size_t at = plane0 + (size_t)g * a.HW + p;
+                    if (a.out_f32) a.out_f32[at] = r;
+                    if (a.out_u8) a.out_u8[at] = (uint8_t)rintf(255.0f * r);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace rinr

@@ -4,6 +4,8 @@ The whole batch is decoded on the GPU; the oracle checks a seeded sample of slot
 pixel (plus the first and last slot), and properties that hold at any size are checked on
 everything: range, uint8 = rint(255 * fp32), repeated ids give identical planes.
 """
+import functools
+
 import numpy as np
 import pytest
 
@@ -14,18 +16,25 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-3
 
 
-@pytest.mark.parametrize("k,n_sample", [(1, 64), (2, 512), (3, 96), (4, 32), (5, 32)])
-def test_full_size_workload(k, n_sample):
-    import torch
+@functools.lru_cache(maxsize=2)
+def packed_workload(k):
     w = synth.workload(k)
-    st = rinr.Store(rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi))
+    return w, rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)
+
+
+@pytest.mark.parametrize("mode", [0, rinr.FLAG_FP32_MFMA], ids=["split-fp16", "fp32-mfma"])
+@pytest.mark.parametrize("k,n_sample", [(1, 64), (2, 512), (3, 96), (4, 32), (5, 32)])
+def test_full_size_workload(k, n_sample, mode):
+    import torch
+    w, blob = packed_workload(k)
+    st = rinr.Store(blob)
     ids = torch.from_numpy(w.image_ids).cuda()
     if w.out_u8:
-        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8)
+        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8, mode)
         u8 = u8.cpu().numpy()
     else:
-        f32, u8 = st.decode_batch(ids, w.H, w.W), None
-    raw = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, rinr.FLAG_NO_CLAMP).cpu().numpy()
+        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode), None
+    raw = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy()
     f32 = f32.cpu().numpy()
     assert st.status() == 0
     info = st.last_launch_info()
@@ -49,5 +58,5 @@ def test_full_size_workload(k, n_sample):
     if u8 is not None:
         ref8 = np.rint(255.0 * np.clip(ref_raw, 0.0, 1.0)).astype(np.int32)
         assert np.abs(u8[pick].astype(np.int32) - ref8).max() <= 1
-    print(f"workload {k}: {len(pick)} slots checked, max-abs {err:.2e}, launch {info}")
+    print(f"workload {k} mode {mode}: {len(pick)} slots checked, max-abs {err:.2e}, launch {info}")
     st.close()

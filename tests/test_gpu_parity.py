@@ -43,6 +43,7 @@ def image_like(models):
 
 
 def check_workload(torch, w, models=None, tile=DEFAULT_TILE, u8=False):
+    """Both matrix paths (default split-precision fp16 MFMA, and fp32 MFMA) against the oracle."""
     models = models if models is not None else w.models
     rinr.tune(0, tile)
     try:
@@ -51,25 +52,30 @@ def check_workload(torch, w, models=None, tile=DEFAULT_TILE, u8=False):
         rinr.tune(0, DEFAULT_TILE)
     ids = ids_dev(torch, w.image_ids)
     ref_nc = oracle.decode(models, w.image_ids, w.H, w.W, w.w0, w.coord_lo, w.coord_hi, clamp=False)
-    got_nc = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, rinr.FLAG_NO_CLAMP).cpu().numpy().astype(np.float64)
-    err_nc = np.abs(got_nc - ref_nc).max()
-    assert err_nc <= TOL, f"unclamped max-abs {err_nc}"
     ref, ref8 = oracle.decode(models, w.image_ids, w.H, w.W, w.w0, w.coord_lo, w.coord_hi, want_u8=True)
-    got = st.decode_batch(ids, w.H, w.W).cpu().numpy()
-    assert got.min() >= 0.0 and got.max() <= 1.0
-    assert np.abs(got.astype(np.float64) - ref).max() <= TOL
-    if u8:
-        g32, g8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8)
-        assert np.array_equal(g32.cpu().numpy(), got)               # same kernel, same bits
-        g8 = g8.cpu().numpy()
-        assert np.abs(g8.astype(np.int32) - ref8.astype(np.int32)).max() <= 1
-        only8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_U8).cpu().numpy()
-        assert np.array_equal(only8, g8)
-        # the uint8 is the rounding of the fp32 the kernel produced
-        assert np.array_equal(g8, np.rint(255.0 * got.astype(np.float32)).astype(np.uint8))
+    worst = 0.0
+    for mode in (0, rinr.FLAG_FP32_MFMA):
+        got_nc = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy().astype(np.float64)
+        err_nc = np.abs(got_nc - ref_nc).max()
+        assert err_nc <= TOL, f"mode {mode}: unclamped max-abs {err_nc}"
+        worst = max(worst, err_nc)
+        got = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode).cpu().numpy()
+        assert got.min() >= 0.0 and got.max() <= 1.0
+        assert np.abs(got.astype(np.float64) - ref).max() <= TOL
+        if mode == 0:
+            assert np.array_equal(st.decode_batch(ids, w.H, w.W).cpu().numpy(), got)   # plain entry point = default mode
+        if u8:
+            g32, g8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8, mode)
+            assert np.array_equal(g32.cpu().numpy(), got)               # same kernel, same bits
+            g8 = g8.cpu().numpy()
+            assert np.abs(g8.astype(np.int32) - ref8.astype(np.int32)).max() <= 1
+            only8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_U8, mode).cpu().numpy()
+            assert np.array_equal(only8, g8)
+            # the uint8 is the rounding of the fp32 the kernel produced
+            assert np.array_equal(g8, np.rint(255.0 * got.astype(np.float32)).astype(np.uint8))
     assert st.status() == 0
     st.close()
-    return err_nc
+    return worst
 
 
 # ---- dequantise / expand stage: bit-exact against the oracle ------------------------------------------------
