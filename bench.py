@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=0, help="experiment: MFMA tile rows for widths 32/64 (16 or 32)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
-    ap.add_argument("--stagger", type=int, default=-1)
+    ap.add_argument("--fp32-mfma", action="store_true", help="time the fp32 MFMA kernels instead of the default split-precision path")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="run only a plain device-to-device copy of MIB MiB per step (counter calibration) and exit")
     args = ap.parse_args()
@@ -75,8 +75,8 @@ def main() -> int:
         rinr.tune(1, args.blocks_per_cu)
     if args.threads:
         rinr.tune(2, args.threads)
-    if args.stagger >= 0:
-        rinr.tune(3, args.stagger)
+    if args.fp32_mfma:
+        rinr.tune(3, 1)
 
     w = synth.workload(args.config)
     blob = rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)

@@ -170,8 +170,7 @@ int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
  * knob 1: 0 = split each slot's pixels over workgroups by the built-in cost model; else a
  *         fixed grid target in workgroups per compute unit (1..1024).
  * knob 2: threads per workgroup: 0 = by image size, or 256 / 512.
- * knob 3: experiment: start delay of some wavefronts (default 0).
- * knob 4: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA). */
+ * knob 3: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA). */
 int rinr_tune(int knob, int value);
 
 const char *rinr_strerror(int code);

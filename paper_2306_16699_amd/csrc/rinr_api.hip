@@ -31,7 +31,6 @@ int g_tile_rows_wide = 32;      // MFMA tile for classes 2 and 4: 16 (16x16x4) o
 int g_blocks_per_cu = 0;        // 0 = modelled split; else a fixed grid target in workgroups per CU
 int g_threads = 0;              // 0 = choose by image size, else 256 or 512
 int g_force_fp32 = 0;           // 1 = always use the fp32 MFMA kernel
-int g_stagger = 0;              // start delay of the upper half of the wavefronts, in units of 64 clocks
 
 typedef void (*decode_fn)(const DecodeArgs);
 typedef void (*debug_fn)(const uint8_t *, int64_t, int, uint32_t, float *, float *);
@@ -124,8 +123,7 @@ extern "C" int rinr_tune(int knob, int value) {
         case 0: if (value != 16 && value != 32) return RINR_E_ARG; g_tile_rows_wide = value; return RINR_OK;
         case 1: if (value < 0 || value > 1024) return RINR_E_ARG; g_blocks_per_cu = value; return RINR_OK;
         case 2: if (value != 0 && value != 256 && value != 512) return RINR_E_ARG; g_threads = value; return RINR_OK;
-        case 4: if (value != 0 && value != 1) return RINR_E_ARG; g_force_fp32 = value; return RINR_OK;
-        case 3: if (value < 0 || value > 0x3FFFF) return RINR_E_ARG; g_stagger = value; return RINR_OK;
+        case 3: if (value != 0 && value != 1) return RINR_E_ARG; g_force_fp32 = value; return RINR_OK;
         default: return RINR_E_ARG;
     }
 }
@@ -290,7 +288,6 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     a.span = h.coord_hi - h.coord_lo;
     a.pre = (float)((double)h.w0 / (2.0 * M_PI));
     a.no_clamp = (opts->flags & RINR_FLAG_NO_CLAMP) ? 1u : 0u;
-    a.stagger = (uint32_t)g_stagger;
     a.neg1 = -1.0f;
     const bool xdl = s->xdl_ok && !(opts->flags & RINR_FLAG_FP32_MFMA) && !g_force_fp32;
 

@@ -200,7 +200,6 @@ struct DecodeArgs {
     uint32_t cls;                 // width class this launch serves (padded width / 16)
     uint32_t no_clamp;
     uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
-    uint32_t stagger;             // experiment: start delay of some wavefronts, in units of 64 clocks
     float neg1;                   // -1.0f, passed as data (keeps a subtraction in mixed-precision fma form)
 };
 
@@ -255,19 +254,19 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
         for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
     }
     expand_model<TM, WP>(lds, stage, L, a.pre, tid, nthreads);   // zero-fill barrier orders the staging too
+    // Tiles are handed out through a counter in LDS (the first word of the staging area, dead by
+    // now): wavefronts sharing a SIMD do not progress at the same rate.
+    uint32_t *next_tile = stage;
+    if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
+    __syncthreads();
 
-    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int g = lane / TM;
-    // Wavefronts w and w + nwaves/2 share a SIMD.  Started together they stay in lock step and
-    // reach their sine / output phases (no MFMA work) at the same time; a one-off delay of one
-    // of them keeps the matrix pipe fed by the other meanwhile.
-    if ((wave >> (a.stagger >> 16)) & 1)
-        for (uint32_t q = 0; q < (a.stagger & 0xFFFF); q += 64) __builtin_amdgcn_s_sleep(64);
     const float *wfirst = lds + LY::off_first() + lane * MTS;
     const float *wout = lds + LY::off_out(L) + g * KSTEPS * 4;
     const float ob0 = lds[LY::off_outb(L) + 0], ob1 = lds[LY::off_outb(L) + 1], ob2 = lds[LY::off_outb(L) + 2];
 
-    for (uint32_t tile = tile0 + wave; tile < tile1; tile += nwaves) {
+    for (uint32_t tile = tile0 + wave; tile < tile1;) {
         float Bv[NT][KSTEPS];
         acc_t D[NT][MT];
         // ---- coordinates of this lane's pixel in each of its NT tiles; lane group 0 feeds x, 1 feeds y
@@ -377,6 +376,9 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
                 dst[2 * (size_t)a.HW] = (uint8_t)rintf(255.0f * r2);
             }
         }
+        uint32_t nt_ = 0;
+        if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
+        tile = __builtin_amdgcn_readfirstlane(nt_);
     }
 }
 

@@ -26,8 +26,13 @@ typedef float f2v __attribute__((ext_vector_type(2)));
 // A hidden layer takes the two-term integer form when its codes are exact in fp16 and the
 // scale is a usable multiplier; otherwise its dequantised fp32 weights are split hi/lo.
 __host__ __device__ inline bool xdl_int_layer(uint32_t bits, float scale_pre) {
+#ifdef RINR_XDL_ALL_RAW
+    (void)bits; (void)scale_pre;
+    return false;
+#else
     const float a = scale_pre < 0 ? -scale_pre : scale_pre;
     return bits >= 2 && bits <= 8 && a >= 1e-30f && a <= 1e30f;
+#endif
 }
 
 struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
@@ -138,14 +143,23 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
     __syncthreads();
 }
 
+#ifdef RINR_EXP_NOMFMA
+__device__ __forceinline__ f32x4 mfma32h(h8v a, h8v b, f32x4 c) { c[0] += (float)a[0] * (float)b[0]; c[1] += (float)a[1]; c[2] += (float)b[2]; c[3] += (float)a[3]; return c; }
+#else
 __device__ __forceinline__ f32x4 mfma32h(h8v a, h8v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+#endif
 __device__ __forceinline__ f32x4 mfma16h(h4v a, h4v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
 
 // sine of the four accumulator values of one tile, then the exact hi/lo split of the results.
 // neg1 is -1.0f passed as data so that h - float(hi) stays a single mixed-precision fma.
 __device__ __forceinline__ void sine_split(const f32x4 d, float scale, float neg1, h4v &hi, h4v &lo) {
+#ifdef RINR_EXP_NOSIN
+    const f2v p0 = {d[0] * scale, d[1] * scale};
+    const f2v p1 = {d[2] * scale, d[3] * scale};
+#else
     const f2v p0 = {sin_rev(d[0] * scale), sin_rev(d[1] * scale)};
     const f2v p1 = {sin_rev(d[2] * scale), sin_rev(d[3] * scale)};
+#endif
     const h2v a0 = __builtin_convertvector(p0, h2v), a1 = __builtin_convertvector(p1, h2v);
     const f2v r0 = {__builtin_fmaf((float)a0[0], neg1, p0[0]), __builtin_fmaf((float)a0[1], neg1, p0[1])};
     const f2v r1 = {__builtin_fmaf((float)a1[0], neg1, p1[0]), __builtin_fmaf((float)a1[1], neg1, p1[1])};
@@ -154,11 +168,115 @@ __device__ __forceinline__ void sine_split(const f32x4 d, float scale, float neg
     lo = (h4v){b0[0], b0[1], b1[0], b1[1]};
 }
 
+// ---- per-wavefront state of one half (two 16-pixel tiles = 32 pixels) of a 64-pixel tile ----------
+template <int MT> struct XHalf {
+    static constexpr int KJ = MT / 2, KJA = KJ ? KJ : 1;
+    h8v Hh[2][KJA], Hl[2][KJA];     // activations as fp16 hi / lo, operand of the 32-deep k-steps
+    h4v Hh4[2], Hl4[2];             // ... of the 16-deep step (odd MT)
+    f32x4 D[2][MT];                 // accumulators
+};
+
+// sine + split of all accumulators of a half: 32*MT VALU instructions (x4 with the scale multiply)
+template <int MT>
+__device__ __forceinline__ void xdl_epilogue(XHalf<MT> &H, float scale, float neg1) {
+    constexpr int KJ = MT / 2;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            h4v hi, lo;
+            sine_split(H.D[nt][t], scale, neg1, hi, lo);
+            if (t < 2 * KJ) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    H.Hh[nt][t >> 1][(t & 1) * 4 + v] = hi[v];
+                    H.Hl[nt][t >> 1][(t & 1) * 4 + v] = lo[v];
+                }
+            } else { H.Hh4[nt] = hi; H.Hl4[nt] = lo; }
+        }
+}
+
+// MFMAs of one hidden layer for a half.  LO: the layer has a low weight part (three terms).
+template <int MT, bool LO>
+__device__ __forceinline__ void xdl_hidden(XHalf<MT> &H, const char *lds, const XLayer el, int lane, int g) {
+    constexpr int KJ = MT / 2, K16 = MT % 2;
+    const h8v *ah = (const h8v *)(lds + el.off_hi) + lane;
+    const h8v *al = (const h8v *)(lds + el.off_lo) + lane;
+    const h4v *ah4 = (const h4v *)(lds + el.off_hi + KJ * MT * 1024) + lane;
+    const h4v *al4 = (const h4v *)(lds + el.off_lo + KJ * MT * 1024) + lane;
+    const f32x4 *bt = (const f32x4 *)(lds + el.off_bias) + g;
+#pragma unroll
+    for (int j = 0; j < KJ; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#ifdef RINR_EXP_NOLDS
+            h8v av = H.Hh[0][0]; av[0] += (_Float16)(j * MT + mt);
+            h8v aw = av;
+#else
+            const h8v av = ah[(j * MT + mt) * 64];
+            h8v aw;
+            if (LO) aw = al[(j * MT + mt) * 64];
+#endif
+            f32x4 c;
+            if (j == 0) c = bt[mt * 4];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma32h(av, H.Hh[nt][j], j == 0 ? c : H.D[nt][mt]);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma32h(av, H.Hl[nt][j], H.D[nt][mt]);
+            if (LO) {
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma32h(aw, H.Hh[nt][j], H.D[nt][mt]);
+            }
+        }
+    if (K16) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const h4v av = ah4[mt * 64];
+            h4v aw;
+            if (LO) aw = al4[mt * 64];
+            f32x4 c;
+            if (KJ == 0) c = bt[mt * 4];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma16h(av, H.Hh4[nt], KJ == 0 ? c : H.D[nt][mt]);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma16h(av, H.Hl4[nt], H.D[nt][mt]);
+            if (LO) {
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma16h(aw, H.Hh4[nt], H.D[nt][mt]);
+            }
+        }
+    }
+}
+
+// Tell the scheduler to issue the block just written as: a first batch of LDS reads, then NM x
+// (1 MFMA, its share of the NV vector-ALU ops), feeding the remaining NDS LDS reads in between,
+// so that the matrix pipe works on one half while the ALU does the other half's sine and split.
+template <int NM, int NV, int NDS, int I> struct XInterleave {
+    static __device__ __forceinline__ void run() {
+        constexpr int FIRST = NDS < 6 ? NDS : 6;
+        constexpr int PER = (NV * (I + 1)) / NM - (NV * I) / NM;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (PER > 0) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
+        if constexpr (FIRST + I < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        XInterleave<NM, NV, NDS, I + 1>::run();
+    }
+};
+template <int NM, int NV, int NDS> struct XInterleave<NM, NV, NDS, NM> {
+    static __device__ __forceinline__ void run() {}
+};
+template <int NM, int NV, int NDS> __device__ __forceinline__ void xdl_interleave() {
+    constexpr int FIRST = NDS < 6 ? NDS : 6;
+    __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);
+    XInterleave<NM, NV, NDS, 0>::run();
+}
+
 template <int MT, int NTHREADS>
 __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a) {
     typedef XLayout<MT> LY;
-    constexpr int KJ = LY::KJ, K16 = LY::K16, NT = 4;
-    constexpr int KJA = KJ ? KJ : 1;           // array extents must not be zero
+    constexpr int KJ = LY::KJ, K16 = LY::K16;
+    constexpr int NM_INT = 2 * MT * (KJ + K16) * 2, NM_RAW = 2 * MT * (KJ + K16) * 3;   // MFMAs per half-layer
+    constexpr int NV = 32 * MT;                 // ALU ops of a half's epilogue: 8*MT activations x (mul, sin, cvt/2, fma, cvt/2)
+    constexpr int ND_INT = (KJ + K16) * MT + MT, ND_RAW = 2 * (KJ + K16) * MT + MT;     // LDS reads per half-layer
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     char *lds = (char *)lds_f;
 
@@ -193,27 +311,38 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
         uint4 *dst = (uint4 *)stage;
         for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
     }
+    // Tiles are handed out through a counter in LDS (it reuses the first word of the staging area,
+    // which is dead once the model is expanded): the SIMD arbiter favours its older wavefront, so
+    // with a fixed split the favoured waves would finish early and leave the others running alone.
     xdl_expand_model<MT>(lds, stage, L, a.pre, tid, nthreads, a.stage_off << 2);
+    uint32_t *next_tile = stage;
+    if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
+    __syncthreads();
 
-    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, n = lane & 15;
-    if ((wave >> (a.stagger >> 16)) & 1)
-        for (uint32_t q = 0; q < (a.stagger & 0xFFFF); q += 64) __builtin_amdgcn_s_sleep(64);
     const XLayer *tab = (const XLayer *)lds;
     const float neg1 = a.neg1;
+    const XLayer e0 = tab[0], eo = tab[L - 1];
 
-    for (uint32_t tile = tile0 + wave; tile < tile1; tile += nwaves) {
-        h8v Hh[NT][KJA], Hl[NT][KJA];
-        h4v Hh4[NT], Hl4[NT];
-        f32x4 D[NT][MT];
+#ifdef RINR_EXP_TIMING
+    unsigned long long tacc[4] = {0, 0, 0, 0};
+#define RINR_T(i) { const unsigned long long now = __builtin_readcyclecounter(); tacc[i] += now - tprev; tprev = now; }
+#else
+#define RINR_T(i)
+#endif
+    for (uint32_t tile = tile0 + wave; tile < tile1;) {
+#ifdef RINR_EXP_TIMING
+        unsigned long long tprev = __builtin_readcyclecounter();
+#endif
+        XHalf<MT> X, Y;
         // ---- first layer: coordinates as hi/lo halfs in lane group 0; k slots (xh, yh, xl, yl, xh, yh, 0, 0)
         {
-            const XLayer e0 = tab[0];
             const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
             const f32x4 *bt = (const f32x4 *)(lds + e0.off_bias) + g;
-            h8v b0[NT];
+            h8v b0[4];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+            for (int nt = 0; nt < 4; ++nt) {
                 uint32_t p = (tile << 6) + nt * 16 + n;
                 p = min(p, a.HW - 1);
                 const uint32_t row = p / a.W, col = p - row * a.W;
@@ -228,120 +357,86 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
             for (int mt = 0; mt < MT; ++mt) {
                 const h8v av = a0[mt * 64];
                 const f32x4 c = bt[mt * 4];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) D[nt][mt] = mfma32h(av, b0[nt], c);
+                X.D[0][mt] = mfma32h(av, b0[0], c);
+                X.D[1][mt] = mfma32h(av, b0[1], c);
+                Y.D[0][mt] = mfma32h(av, b0[2], c);
+                Y.D[1][mt] = mfma32h(av, b0[3], c);
             }
         }
-        float scale = 1.0f;
-        for (int l = 1; l < L; ++l) {
-            // ---- sine + split of layer l-1's accumulators -> operands of layer l
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    h4v hi, lo;
-                    sine_split(D[nt][t], scale, neg1, hi, lo);
-                    if (t < 2 * KJ) {
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) { Hh[nt][t >> 1][(t & 1) * 4 + v] = hi[v]; Hl[nt][t >> 1][(t & 1) * 4 + v] = lo[v]; }
-                    } else { Hh4[nt] = hi; Hl4[nt] = lo; }
-                }
-            if (l == L - 1) break;
-            // ---- hidden layer l
+        xdl_epilogue<MT>(X, 1.0f, neg1);
+        RINR_T(0)
+        // ---- hidden layers, software-pipelined over the two halves:
+        //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
+        float scale_prev = 1.0f;
+        for (int l = 1; l < L - 1; ++l) {
             const XLayer el = tab[l];
-            scale = el.scale;
-            const h8v *ah = (const h8v *)(lds + el.off_hi) + lane;
-            const h8v *al = (const h8v *)(lds + el.off_lo) + lane;
-            const h4v *ah4 = (const h4v *)(lds + el.off_hi + KJ * MT * 1024) + lane;
-            const h4v *al4 = (const h4v *)(lds + el.off_lo + KJ * MT * 1024) + lane;
-            const f32x4 *bt = (const f32x4 *)(lds + el.off_bias) + g;
-            const bool has_lo = el.off_lo != 0;
-            if (!has_lo) {
-#pragma unroll
-                for (int j = 0; j < KJ; ++j)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const h8v av = ah[(j * MT + mt) * 64];
-                        const f32x4 c = bt[mt * 4];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            D[nt][mt] = mfma32h(av, Hh[nt][j], j == 0 ? c : D[nt][mt]);
-                            D[nt][mt] = mfma32h(av, Hl[nt][j], D[nt][mt]);
-                        }
-                    }
-                if (K16) {
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const h4v av = ah4[mt * 64];
-                        const f32x4 c = bt[mt * 4];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            D[nt][mt] = mfma16h(av, Hh4[nt], KJ == 0 ? c : D[nt][mt]);
-                            D[nt][mt] = mfma16h(av, Hl4[nt], D[nt][mt]);
-                        }
-                    }
-                }
+            if (el.off_lo == 0) {
+                xdl_hidden<MT, false>(X, lds, el, lane, g);
+                xdl_epilogue<MT>(Y, scale_prev, neg1);
+#ifndef RINR_XDL_MERGE
+                xdl_interleave<NM_INT, NV, ND_INT>();
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+                xdl_hidden<MT, false>(Y, lds, el, lane, g);
+                xdl_epilogue<MT>(X, el.scale, neg1);
+#ifndef RINR_XDL_MERGE
+                xdl_interleave<NM_INT, NV, ND_INT>();
+#else
+                xdl_interleave<2 * NM_INT, 2 * NV, 2 * ND_INT>();
+#endif
             } else {
-#pragma unroll
-                for (int j = 0; j < KJ; ++j)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const h8v av = ah[(j * MT + mt) * 64], aw = al[(j * MT + mt) * 64];
-                        const f32x4 c = bt[mt * 4];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            D[nt][mt] = mfma32h(av, Hh[nt][j], j == 0 ? c : D[nt][mt]);
-                            D[nt][mt] = mfma32h(av, Hl[nt][j], D[nt][mt]);
-                            D[nt][mt] = mfma32h(aw, Hh[nt][j], D[nt][mt]);
-                        }
-                    }
-                if (K16) {
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const h4v av = ah4[mt * 64], aw = al4[mt * 64];
-                        const f32x4 c = bt[mt * 4];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            D[nt][mt] = mfma16h(av, Hh4[nt], KJ == 0 ? c : D[nt][mt]);
-                            D[nt][mt] = mfma16h(av, Hl4[nt], D[nt][mt]);
-                            D[nt][mt] = mfma16h(aw, Hh4[nt], D[nt][mt]);
-                        }
-                    }
-                }
+                xdl_hidden<MT, true>(X, lds, el, lane, g);
+                xdl_epilogue<MT>(Y, scale_prev, neg1);
+#ifndef RINR_XDL_MERGE
+                xdl_interleave<NM_RAW, NV, ND_RAW>();
+                __builtin_amdgcn_sched_barrier(0);
+#endif
+                xdl_hidden<MT, true>(Y, lds, el, lane, g);
+                xdl_epilogue<MT>(X, el.scale, neg1);
+#ifndef RINR_XDL_MERGE
+                xdl_interleave<NM_RAW, NV, ND_RAW>();
+#else
+                xdl_interleave<2 * NM_RAW, 2 * NV, 2 * ND_RAW>();
+#endif
             }
+            scale_prev = el.scale;
         }
+        RINR_T(1)
+        xdl_epilogue<MT>(Y, scale_prev, neg1);
+        RINR_T(2)
         // ---- output layer width -> 3: one 16-row tile, channel c in row 4c = lane group c, register 0
         {
-            const XLayer eo = tab[L - 1];
             const h8v *ah = (const h8v *)(lds + eo.off_hi) + lane;
             const h8v *al = (const h8v *)(lds + eo.off_lo) + lane;
             const h4v *ah4 = (const h4v *)(lds + eo.off_hi + KJ * 1024) + lane;
             const h4v *al4 = (const h4v *)(lds + eo.off_lo + KJ * 1024) + lane;
             const f32x4 c = ((const f32x4 *)(lds + eo.off_bias))[g];
-            f32x4 O[NT];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) O[nt] = c;
+            f32x4 O[4] = {c, c, c, c};
 #pragma unroll
             for (int j = 0; j < KJ; ++j) {
                 const h8v av = ah[j * 64], aw = al[j * 64];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    O[nt] = mfma32h(av, Hh[nt][j], O[nt]);
-                    O[nt] = mfma32h(av, Hl[nt][j], O[nt]);
-                    O[nt] = mfma32h(aw, Hh[nt][j], O[nt]);
+                for (int nt = 0; nt < 4; ++nt) {
+                    const h8v bh = nt < 2 ? X.Hh[nt][j] : Y.Hh[nt - 2][j];
+                    const h8v bl = nt < 2 ? X.Hl[nt][j] : Y.Hl[nt - 2][j];
+                    O[nt] = mfma32h(av, bh, O[nt]);
+                    O[nt] = mfma32h(av, bl, O[nt]);
+                    O[nt] = mfma32h(aw, bh, O[nt]);
                 }
             }
             if (K16) {
                 const h4v av = ah4[0], aw = al4[0];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    O[nt] = mfma16h(av, Hh4[nt], O[nt]);
-                    O[nt] = mfma16h(av, Hl4[nt], O[nt]);
-                    O[nt] = mfma16h(aw, Hh4[nt], O[nt]);
+                for (int nt = 0; nt < 4; ++nt) {
+                    const h4v bh = nt < 2 ? X.Hh4[nt] : Y.Hh4[nt - 2];
+                    const h4v bl = nt < 2 ? X.Hl4[nt] : Y.Hl4[nt - 2];
+                    O[nt] = mfma16h(av, bh, O[nt]);
+                    O[nt] = mfma16h(av, bl, O[nt]);
+                    O[nt] = mfma16h(aw, bh, O[nt]);
                 }
             }
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+            for (int nt = 0; nt < 4; ++nt) {
                 float r = O[nt][0];
                 if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
                 const uint32_t p = (tile << 6) + nt * 16 + n;
@@ -352,7 +447,17 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
                 }
             }
         }
+        RINR_T(3)
+        uint32_t nt_ = 0;
+        if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
+        tile = __builtin_amdgcn_readfirstlane(nt_);
     }
+#ifdef RINR_EXP_TIMING
+    if (blockIdx.x == 7 && lane == 0) {
+        unsigned long long *dbg = (unsigned long long *)a.out_u8;     // experiment only: timings overwrite the uint8 output
+        for (int i = 0; i < 4; ++i) dbg[wave * 4 + i] = tacc[i];
+    }
+#endif
 }
 
 }  // namespace rinr

@@ -13,7 +13,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-SO_PATH = os.path.join(_HERE, "librinr.so")
+SO_PATH = os.environ.get("RINR_LIB") or os.path.join(_HERE, "librinr.so")   # RINR_LIB: load another build of the library
 
 OK = 0
 OUT_F32, OUT_U8, OUT_F32_AND_U8 = 1, 2, 3
