@@ -23,6 +23,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 FLOP/clk x 2.4 GHz)
+PEAK_FP16_MFMA_TFLOPS = 2500.0    # MI355X dense fp16 matrix peak
+PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3 T lane-operations/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+
+
+def alu_ops_per_pixel(model) -> int:
+    """Vector-ALU operations the split-precision path needs per pixel (algorithmic, one per lane):
+    per sine-layer output: sine, hi conversion (1/2), residual, lo conversion (1/2) = 3, plus the
+    dequantisation scale where the layer is stored as 2..8-bit codes (it multiplies the accumulator)."""
+    n = 0
+    for l, ly in enumerate(model.layers[:-1]):
+        n += ly.n_out * (3 + (1 if (l > 0 and 2 <= ly.bits <= 8) else 0))
+    return n
 
 
 def host_threads() -> int:
@@ -75,8 +87,6 @@ def main() -> int:
         rinr.tune(1, args.blocks_per_cu)
     if args.threads:
         rinr.tune(2, args.threads)
-    if args.fp32_mfma:
-        rinr.tune(3, 1)
 
     w = synth.workload(args.config)
     blob = rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)
@@ -87,36 +97,58 @@ def main() -> int:
     out8 = torch.empty((n, 3, H, W), dtype=torch.uint8, device="cuda") if w.out_u8 else None
     dtype = rinr.OUT_F32_AND_U8 if w.out_u8 else rinr.OUT_F32
 
-    def step():
-        st.decode_batch_ex(ids, H, W, dtype, 0, out=out, out_u8=out8)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()                      # same stream the library launches on (torch's current stream)
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall_ms = (t1 - t0) * 1e3 / args.steps
-    kern_ms = ev0.elapsed_time(ev1) / args.steps
-    assert st.status() == 0
-    info = st.last_launch_info()
+    def timed(flags):
+        def step():
+            st.decode_batch_ex(ids, H, W, dtype, flags, out=out, out_u8=out8)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()                      # same stream the library launches on (torch's current stream)
+        for _ in range(args.steps):
+            step()
+        ev1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / args.steps, ev0.elapsed_time(ev1) / args.steps, st.last_launch_info()
 
     pixels = n * H * W
     flop_px = np.array([synth.dense_flop_per_pixel(w.models[int(i)]) for i in w.image_ids], dtype=np.float64)
     flops = float(flop_px.sum()) * H * W
-    achieved = flops / (kern_ms * 1e-3) / 1e12
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"decode_cfg{args.config}_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    alu_px = np.array([alu_ops_per_pixel(w.models[int(i)]) for i in w.image_ids], dtype=np.float64)
+    alu_ops = float(alu_px.sum()) * H * W
+
+    def traffic_of(tag):
+        tpath = os.path.join(ROOT, "profiles", f"decode_{tag}_cfg{args.config}_traffic.json")
+        if os.path.exists(tpath):
+            try:
+                return json.load(open(tpath)).get("hbm_bytes_per_launch")
+            except Exception:
+                return None
+        return None
+
+    def mfma_roofline(kern_ms, tag):
+        ach = flops / (kern_ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic_of(tag), "kernel_ms": kern_ms,
+                "flop_per_launch": flops, "kernel": "decode_kernel (fp32 MFMA)"}
+
+    if args.fp32_mfma:
+        wall_ms, kern_ms, info = timed(rinr.FLAG_FP32_MFMA)
+        roof, dtype_name, alt = mfma_roofline(kern_ms, "fp32mfma"), "f32", None
+    else:
+        wall_ms, kern_ms, info = timed(0)
+        ach = alu_ops / (kern_ms * 1e-3) / 1e12
+        roof = {"bound": "alu", "achieved": ach, "peak": PEAK_VALU_TOPS, "unit": "Top/s (vector-ALU lane operations)",
+                "frac": ach / PEAK_VALU_TOPS, "traffic": traffic_of("xdl"), "kernel_ms": kern_ms,
+                "alu_ops_per_launch": alu_ops, "kernel": "decode_xdl_kernel (fp16 hi+lo operands on MFMA, fp32 accumulate)",
+                "matrix_algorithmic_tflops": flops / (kern_ms * 1e-3) / 1e12, "matrix_fp16_peak_tflops": PEAK_FP16_MFMA_TFLOPS}
+        dtype_name = "f16x2-split operands, f32 accumulate"
+        w2, k2, i2 = timed(rinr.FLAG_FP32_MFMA)
+        alt = {"mode": "RINR_FLAG_FP32_MFMA", "value": pixels / (w2 * 1e-3), "unit": "pixels/s", "ms_per_step": w2,
+               "roofline": mfma_roofline(k2, "fp32mfma"), "launch": i2}
+    assert st.status() == 0
 
     res = {
         "metric": "decoded pixels/sec (and images/sec) on 1 MI355X; % of MFMA/VALU FLOP peak",
@@ -126,15 +158,15 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": dtype_name, "data": "synthetic",
         "config": {"workload": w.name, "images": n, "H": H, "W": W,
                    "outputs": "fp32+uint8 NCHW" if w.out_u8 else "fp32 NCHW",
-                   "flop_per_pixel_mean": float(flop_px.mean()),
+                   "flop_per_pixel_mean": float(flop_px.mean()), "alu_ops_per_pixel_mean": float(alu_px.mean()),
                    "launch": info},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic,
-                     "kernel_ms": kern_ms, "flop_per_launch": flops},
+        "roofline": roof,
     }
+    if alt is not None:
+        res["fp32_mfma_mode"] = alt
 
     if not args.no_cpu_baseline:
         from oracle import oracle

@@ -140,6 +140,10 @@ typedef struct {
  * NO_CLAMP with a uint8 output) are returned before anything is enqueued.  An id outside
  * [0, n_models) cannot be seen from the host: that slot is written as zeros and a sticky
  * device counter is incremented (read it with rinr_store_status).
+ * Domain: every sine argument w0*(Wx+b) must stay within +-512*pi (the hardware sine's
+ * range; sine networks stay within a few tens of radians).  The default split-precision
+ * kernels also need |w * w0/2pi| and the coordinate bounds below 6e4 (fp16 range); a store
+ * that breaks this is served by the fp32 MFMA kernels automatically.
  * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL}. */
 int rinr_decode_batch(const rinr_store *models, const int64_t *image_ids, int32_t n,
                       int32_t H, int32_t W, void *out, void *stream);

@@ -24,7 +24,10 @@ inline bool hip_fail(hipError_t e) {
 #define RINR_HIP(call) do { if (hip_fail(call)) return RINR_E_HIP; } while (0)
 
 constexpr uint32_t kLdsLimit = 160 * 1024;   // LDS per workgroup on gfx950
-constexpr int kThreads = 512;                // launch bound of the decode kernels
+#ifndef RINR_MAX_THREADS
+#define RINR_MAX_THREADS 512
+#endif
+constexpr int kThreads = RINR_MAX_THREADS;   // launch bound of the decode kernels
 
 // tuning knobs (see rinr_tune)
 int g_tile_rows_wide = 32;      // MFMA tile for classes 2 and 4: 16 (16x16x4) or 32 (32x32x2)
@@ -122,7 +125,7 @@ extern "C" int rinr_tune(int knob, int value) {
     switch (knob) {
         case 0: if (value != 16 && value != 32) return RINR_E_ARG; g_tile_rows_wide = value; return RINR_OK;
         case 1: if (value < 0 || value > 1024) return RINR_E_ARG; g_blocks_per_cu = value; return RINR_OK;
-        case 2: if (value != 0 && value != 256 && value != 512) return RINR_E_ARG; g_threads = value; return RINR_OK;
+        case 2: if (value != 0 && (value % 64 || value < 64 || value > kThreads)) return RINR_E_ARG; g_threads = value; return RINR_OK;
         case 3: if (value != 0 && value != 1) return RINR_E_ARG; g_force_fp32 = value; return RINR_OK;
         default: return RINR_E_ARG;
     }
@@ -173,7 +176,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         const float pre = (float)((double)sum.header.w0 / (2.0 * M_PI));
         uint32_t need[kMaxClass + 1] = {0, 0, 0, 0, 0};
         double acts[kMaxClass + 1] = {0, 0, 0, 0, 0};
-        s->xdl_ok = true;
+        s->xdl_ok = std::fabs(sum.header.coord_lo) < 60000.0f && std::fabs(sum.header.coord_hi) < 60000.0f;   // coordinates travel as fp16 hi+lo
         for (const IndexEntry &e : s->index) {
             const uint32_t c = e.width == 0 ? 1u : (e.width + 15u) >> 4;
             int n_int = 0, n_raw = 0;
@@ -282,6 +285,12 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     a.n_models = h.n_models;
     a.HW = (uint32_t)HW;
     a.W = (uint32_t)W;
+    {   // exact division of a pixel index (< 2^31) by W as a multiply-high and a shift
+        uint32_t l = 0;
+        while ((1ull << l) < (uint64_t)W) ++l;
+        a.wmagic = l ? (uint32_t)((((uint64_t)1 << (31 + l)) + (uint64_t)W - 1) / (uint64_t)W) : 0u;
+        a.wshift = l ? l - 1 : 0u;
+    }
     a.inv2W = (float)(1.0 / (2.0 * W));
     a.inv2H = (float)(1.0 / (2.0 * H));
     a.lo = h.coord_lo;

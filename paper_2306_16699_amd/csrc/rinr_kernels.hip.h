@@ -191,6 +191,7 @@ struct DecodeArgs {
     unsigned long long *status;   // sticky count of out-of-range ids
     uint64_t n_models;
     uint32_t HW, W;
+    uint32_t wmagic, wshift;      // p / W == umulhi(p, wmagic) >> wshift for p < 2^31; wmagic == 0 means W == 1
     float inv2W, inv2H;           // 1/(2W), 1/(2H)
     float lo, span;               // coordinate = lo + span * (2k+1)/(2n)
     float pre;                    // w0 / (2 pi)
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
         for (int nt = 0; nt < NT; ++nt) {
             uint32_t p = (tile << 6) + nt * TM + (lane % TM);
             p = min(p, a.HW - 1);
-            const uint32_t row = p / a.W, col = p - row * a.W;
+            const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
             const float x = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
             const float y = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
             bx[nt] = g == 0 ? x : (g == 1 ? y : 0.0f);

@@ -31,7 +31,7 @@ __host__ __device__ inline bool xdl_int_layer(uint32_t bits, float scale_pre) {
     return false;
 #else
     const float a = scale_pre < 0 ? -scale_pre : scale_pre;
-    return bits >= 2 && bits <= 8 && a >= 1e-30f && a <= 1e30f;
+    return bits >= 2 && bits <= 8 && a >= 1e-12f && a <= 1e12f;
 #endif
 }
 
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
             for (int nt = 0; nt < 4; ++nt) {
                 uint32_t p = (tile << 6) + nt * 16 + n;
                 p = min(p, a.HW - 1);
-                const uint32_t row = p / a.W, col = p - row * a.W;
+                const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
                 const float x = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
                 const float y = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
                 const _Float16 xh = (_Float16)x, yh = (_Float16)y;
