@@ -173,7 +173,7 @@ int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
  *         (16x16x4 fp32); read at rinr_store_open.
  * knob 1: 0 = split each slot's pixels over workgroups by the built-in cost model; else a
  *         fixed grid target in workgroups per compute unit (1..1024).
- * knob 2: threads per workgroup: 0 = by image size, or 256 / 512.
+ * knob 2: threads per workgroup: 0 = by image size, or a multiple of 64 up to 768.
  * knob 3: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA). */
 int rinr_tune(int knob, int value);
 

@@ -24,15 +24,12 @@ inline bool hip_fail(hipError_t e) {
 #define RINR_HIP(call) do { if (hip_fail(call)) return RINR_E_HIP; } while (0)
 
 constexpr uint32_t kLdsLimit = 160 * 1024;   // LDS per workgroup on gfx950
-#ifndef RINR_MAX_THREADS
-#define RINR_MAX_THREADS 512
-#endif
-constexpr int kThreads = RINR_MAX_THREADS;   // launch bound of the decode kernels
+constexpr int kThreads = 768;                // launch bound of the decode kernels: 12 wavefronts, 3 per SIMD, <= 168 VGPRs
 
 // tuning knobs (see rinr_tune)
 int g_tile_rows_wide = 32;      // MFMA tile for classes 2 and 4: 16 (16x16x4) or 32 (32x32x2)
 int g_blocks_per_cu = 0;        // 0 = modelled split; else a fixed grid target in workgroups per CU
-int g_threads = 0;              // 0 = choose by image size, else 256 or 512
+int g_threads = 0;              // 0 = choose by image size, else a multiple of 64 up to kThreads
 int g_force_fp32 = 0;           // 1 = always use the fp32 MFMA kernel
 
 typedef void (*decode_fn)(const DecodeArgs);
@@ -301,7 +298,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     const bool xdl = s->xdl_ok && !(opts->flags & RINR_FLAG_FP32_MFMA) && !g_force_fp32;
 
     const uint32_t tiles = (uint32_t)((HW + 63) >> 6);
-    const int threads = g_threads ? g_threads : (tiles >= 64 ? 512 : 256);
+    const int threads = g_threads ? g_threads : (tiles >= 96 ? 768 : (tiles >= 64 ? 512 : 256));
     const uint32_t nw = (uint32_t)threads / 64;
 
     const int knob = g_blocks_per_cu * 2 + (xdl ? 1 : 0);

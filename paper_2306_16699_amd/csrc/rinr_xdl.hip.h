@@ -26,13 +26,8 @@ typedef float f2v __attribute__((ext_vector_type(2)));
 // A hidden layer takes the two-term integer form when its codes are exact in fp16 and the
 // scale is a usable multiplier; otherwise its dequantised fp32 weights are split hi/lo.
 __host__ __device__ inline bool xdl_int_layer(uint32_t bits, float scale_pre) {
-#ifdef RINR_XDL_ALL_RAW
-    (void)bits; (void)scale_pre;
-    return false;
-#else
     const float a = scale_pre < 0 ? -scale_pre : scale_pre;
     return bits >= 2 && bits <= 8 && a >= 1e-12f && a <= 1e12f;
-#endif
 }
 
 struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
@@ -143,23 +138,14 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
     __syncthreads();
 }
 
-#ifdef RINR_EXP_NOMFMA
-__device__ __forceinline__ f32x4 mfma32h(h8v a, h8v b, f32x4 c) { c[0] += (float)a[0] * (float)b[0]; c[1] += (float)a[1]; c[2] += (float)b[2]; c[3] += (float)a[3]; return c; }
-#else
 __device__ __forceinline__ f32x4 mfma32h(h8v a, h8v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
-#endif
 __device__ __forceinline__ f32x4 mfma16h(h4v a, h4v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
 
 // sine of the four accumulator values of one tile, then the exact hi/lo split of the results.
 // neg1 is -1.0f passed as data so that h - float(hi) stays a single mixed-precision fma.
 __device__ __forceinline__ void sine_split(const f32x4 d, float scale, float neg1, h4v &hi, h4v &lo) {
-#ifdef RINR_EXP_NOSIN
-    const f2v p0 = {d[0] * scale, d[1] * scale};
-    const f2v p1 = {d[2] * scale, d[3] * scale};
-#else
     const f2v p0 = {sin_rev(d[0] * scale), sin_rev(d[1] * scale)};
     const f2v p1 = {sin_rev(d[2] * scale), sin_rev(d[3] * scale)};
-#endif
     const h2v a0 = __builtin_convertvector(p0, h2v), a1 = __builtin_convertvector(p1, h2v);
     const f2v r0 = {__builtin_fmaf((float)a0[0], neg1, p0[0]), __builtin_fmaf((float)a0[1], neg1, p0[1])};
     const f2v r1 = {__builtin_fmaf((float)a1[0], neg1, p1[0]), __builtin_fmaf((float)a1[1], neg1, p1[1])};
@@ -209,14 +195,9 @@ __device__ __forceinline__ void xdl_hidden(XHalf<MT> &H, const char *lds, const 
     for (int j = 0; j < KJ; ++j)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-#ifdef RINR_EXP_NOLDS
-            h8v av = H.Hh[0][0]; av[0] += (_Float16)(j * MT + mt);
-            h8v aw = av;
-#else
             const h8v av = ah[(j * MT + mt) * 64];
             h8v aw;
             if (LO) aw = al[(j * MT + mt) * 64];
-#endif
             f32x4 c;
             if (j == 0) c = bt[mt * 4];
 #pragma unroll
@@ -325,16 +306,7 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
     const float neg1 = a.neg1;
     const XLayer e0 = tab[0], eo = tab[L - 1];
 
-#ifdef RINR_EXP_TIMING
-    unsigned long long tacc[4] = {0, 0, 0, 0};
-#define RINR_T(i) { const unsigned long long now = __builtin_readcyclecounter(); tacc[i] += now - tprev; tprev = now; }
-#else
-#define RINR_T(i)
-#endif
     for (uint32_t tile = tile0 + wave; tile < tile1;) {
-#ifdef RINR_EXP_TIMING
-        unsigned long long tprev = __builtin_readcyclecounter();
-#endif
         XHalf<MT> X, Y;
         // ---- first layer: coordinates as hi/lo halfs in lane group 0; k slots (xh, yh, xl, yl, xh, yh, 0, 0)
         {
@@ -364,7 +336,6 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
             }
         }
         xdl_epilogue<MT>(X, 1.0f, neg1);
-        RINR_T(0)
         // ---- hidden layers, software-pipelined over the two halves:
         //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
         float scale_prev = 1.0f;
@@ -373,37 +344,23 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
             if (el.off_lo == 0) {
                 xdl_hidden<MT, false>(X, lds, el, lane, g);
                 xdl_epilogue<MT>(Y, scale_prev, neg1);
-#ifndef RINR_XDL_MERGE
                 xdl_interleave<NM_INT, NV, ND_INT>();
                 __builtin_amdgcn_sched_barrier(0);
-#endif
                 xdl_hidden<MT, false>(Y, lds, el, lane, g);
                 xdl_epilogue<MT>(X, el.scale, neg1);
-#ifndef RINR_XDL_MERGE
                 xdl_interleave<NM_INT, NV, ND_INT>();
-#else
-                xdl_interleave<2 * NM_INT, 2 * NV, 2 * ND_INT>();
-#endif
             } else {
                 xdl_hidden<MT, true>(X, lds, el, lane, g);
                 xdl_epilogue<MT>(Y, scale_prev, neg1);
-#ifndef RINR_XDL_MERGE
                 xdl_interleave<NM_RAW, NV, ND_RAW>();
                 __builtin_amdgcn_sched_barrier(0);
-#endif
                 xdl_hidden<MT, true>(Y, lds, el, lane, g);
                 xdl_epilogue<MT>(X, el.scale, neg1);
-#ifndef RINR_XDL_MERGE
                 xdl_interleave<NM_RAW, NV, ND_RAW>();
-#else
-                xdl_interleave<2 * NM_RAW, 2 * NV, 2 * ND_RAW>();
-#endif
             }
             scale_prev = el.scale;
         }
-        RINR_T(1)
         xdl_epilogue<MT>(Y, scale_prev, neg1);
-        RINR_T(2)
         // ---- output layer width -> 3: one 16-row tile, channel c in row 4c = lane group c, register 0
         {
             const h8v *ah = (const h8v *)(lds + eo.off_hi) + lane;
@@ -447,17 +404,10 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
                 }
             }
         }
-        RINR_T(3)
         uint32_t nt_ = 0;
         if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
         tile = __builtin_amdgcn_readfirstlane(nt_);
     }
-#ifdef RINR_EXP_TIMING
-    if (blockIdx.x == 7 && lane == 0) {
-        unsigned long long *dbg = (unsigned long long *)a.out_u8;     // experiment only: timings overwrite the uint8 output
-        for (int i = 0; i < 4; ++i) dbg[wave * 4 + i] = tacc[i];
-    }
-#endif
 }
 
 }  // namespace rinr
