@@ -30,7 +30,7 @@ void orc_dequant(const orc_layer *l, double *w_out)
 
 /* One image: every pixel's centre coordinate through the MLP (Sec. III-A/B). */
 static void decode_one(const orc_model *m, int32_t H, int32_t W, double w0, double lo,
-                       double hi, int clamp, double *out, uint8_t *out8)
+                       double hi, int clamp, const double *aff, const double *norm, double *out, uint8_t *out8)
 {
     const int L = m->n_layers;
     int maxw = 2;
@@ -54,8 +54,15 @@ static void decode_one(const orc_model *m, int32_t H, int32_t W, double w0, doub
     for (int32_t i = 0; i < H; ++i) {
         for (int32_t j = 0; j < W; ++j) {
             /* pixel centres of a [lo, hi] x [lo, hi] grid; component 0 is horizontal */
-            h_prev[0] = lo + (hi - lo) * (2.0 * j + 1.0) / (2.0 * W);
-            h_prev[1] = lo + (hi - lo) * (2.0 * i + 1.0) / (2.0 * H);
+            const double x = lo + (hi - lo) * (2.0 * j + 1.0) / (2.0 * W);
+            const double y = lo + (hi - lo) * (2.0 * i + 1.0) / (2.0 * H);
+            if (aff) {   /* augmentation: affine map of the sampling grid */
+                h_prev[0] = aff[0] * x + aff[1] * y + aff[2];
+                h_prev[1] = aff[3] * x + aff[4] * y + aff[5];
+            } else {
+                h_prev[0] = x;
+                h_prev[1] = y;
+            }
             int64_t off = 0;
             for (int l = 0; l < L; ++l) {
                 const orc_layer *ly = &m->layers[l];
@@ -72,17 +79,18 @@ static void decode_one(const orc_model *m, int32_t H, int32_t W, double w0, doub
             for (int c = 0; c < 3; ++c) {
                 double v = h_prev[c];
                 if (clamp) v = fmin(fmax(v, 0.0), 1.0);
-                out[c * plane + (int64_t)i * W + j] = v;
                 if (out8) out8[c * plane + (int64_t)i * W + j] = (uint8_t)nearbyint(255.0 * v);
+                if (norm) v = v * norm[c] + norm[3 + c];
+                out[c * plane + (int64_t)i * W + j] = v;
             }
         }
     }
     free(wts); free(h_prev); free(h_next);
 }
 
-int orc_decode(const orc_model *models, int64_t n_models, const int64_t *ids, int64_t n,
-               int32_t H, int32_t W, double w0, double lo, double hi, int clamp,
-               double *out_f64, uint8_t *out_u8, int n_threads)
+static int decode_all(const orc_model *models, int64_t n_models, const int64_t *ids, int64_t n,
+                      int32_t H, int32_t W, double w0, double lo, double hi, int clamp,
+                      const double *affine, const double *norm, double *out_f64, uint8_t *out_u8, int n_threads)
 {
     if (!models || !ids || !out_f64 || n < 0 || H <= 0 || W <= 0) return -1;
     if (!clamp && out_u8) return -1;
@@ -97,7 +105,22 @@ int orc_decode(const orc_model *models, int64_t n_models, const int64_t *ids, in
     if (n_threads < 1) n_threads = 1;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(n_threads)
     for (int64_t s = 0; s < n; ++s)
-        decode_one(&models[ids[s]], H, W, w0, lo, hi, clamp, out_f64 + s * img,
-                   out_u8 ? out_u8 + s * img : (uint8_t *)0);
+        decode_one(&models[ids[s]], H, W, w0, lo, hi, clamp, affine ? affine + 6 * s : (const double *)0, norm,
+                   out_f64 + s * img, out_u8 ? out_u8 + s * img : (uint8_t *)0);
     return 0;
+}
+
+int orc_decode(const orc_model *models, int64_t n_models, const int64_t *ids, int64_t n,
+               int32_t H, int32_t W, double w0, double lo, double hi, int clamp,
+               double *out_f64, uint8_t *out_u8, int n_threads)
+{
+    return decode_all(models, n_models, ids, n, H, W, w0, lo, hi, clamp, (const double *)0, (const double *)0,
+                      out_f64, out_u8, n_threads);
+}
+
+int orc_decode_aug(const orc_model *models, int64_t n_models, const int64_t *ids, int64_t n,
+                   int32_t H, int32_t W, double w0, double lo, double hi, int clamp,
+                   const double *affine, const double *norm, double *out_f64, int n_threads)
+{
+    return decode_all(models, n_models, ids, n, H, W, w0, lo, hi, clamp, affine, norm, out_f64, (uint8_t *)0, n_threads);
 }

@@ -50,4 +50,16 @@ int orc_decode(const orc_model *models, int64_t n_models, const int64_t *ids, in
                int32_t H, int32_t W, double w0, double lo, double hi, int clamp,
                double *out_f64, uint8_t *out_u8, int n_threads);
 
+/* Decode with on-GPU-style augmentation (Sec. III-B: augmentation runs on the decoded
+ * batch before the backbone).  Geometric augmentation is a per-slot affine map of the
+ * sampling grid, which a resolution-free decode (Sec. III-B) gets for free:
+ *   (x', y') = (A[0] x + A[1] y + A[2],  A[3] x + A[4] y + A[5])
+ * with (x, y) the pixel-centre coordinate; affine is [n][6] or NULL (identity).
+ * Photometric normalisation is per channel, after the clamp:
+ *   out = value * norm[c] + norm[3 + c];  norm is [6] or NULL (none).
+ * out_u8 is not available here. */
+int orc_decode_aug(const orc_model *models, int64_t n_models, const int64_t *ids, int64_t n,
+                   int32_t H, int32_t W, double w0, double lo, double hi, int clamp,
+                   const double *affine, const double *norm, double *out_f64, int n_threads);
+
 #endif

@@ -49,6 +49,9 @@ def lib():
         L.orc_decode.argtypes = [C.POINTER(_Model), C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                  C.c_double, C.c_double, C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.c_int]
         L.orc_decode.restype = C.c_int
+        L.orc_decode_aug.argtypes = [C.POINTER(_Model), C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                     C.c_double, C.c_double, C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        L.orc_decode_aug.restype = C.c_int
         _lib = L
     return _lib
 
@@ -86,10 +89,12 @@ def dequant(layer) -> np.ndarray:
     return out.reshape(layer.n_out, layer.n_in)
 
 
-def decode(models, image_ids, H, W, w0=30.0, lo=-1.0, hi=1.0, clamp=True, want_u8=False, n_threads=None):
+def decode(models, image_ids, H, W, w0=30.0, lo=-1.0, hi=1.0, clamp=True, want_u8=False, n_threads=None,
+           affine=None, norm=None):
     """Decode slots; only the models that image_ids names are marshalled.
 
     Returns out_f64 [n, 3, H, W] (and out_u8 of the same shape when want_u8).
+    affine: None or [n, 6] per-slot map of the sampling grid; norm: None or (scale[3], shift[3]).
     """
     ids = np.ascontiguousarray(image_ids, dtype=np.int64)
     n = len(ids)
@@ -109,9 +114,18 @@ def decode(models, image_ids, H, W, w0=30.0, lo=-1.0, hi=1.0, clamp=True, want_u
     local_ids = np.ascontiguousarray(inv, dtype=np.int64)
     out = np.empty((n, 3, H, W), dtype=np.float64)
     out8 = np.empty((n, 3, H, W), dtype=np.uint8) if want_u8 else None
-    rc = lib().orc_decode(arr, len(uniq), local_ids.ctypes.data, n, H, W, float(w0), float(lo), float(hi),
-                          1 if clamp else 0, out.ctypes.data, out8.ctypes.data if want_u8 else None,
-                          int(n_threads))
+    if affine is not None or norm is not None:
+        if want_u8:
+            raise ValueError("uint8 output is not defined with augmentation")
+        aff = None if affine is None else np.ascontiguousarray(affine, dtype=np.float64).reshape(n, 6)
+        nrm = None if norm is None else np.ascontiguousarray(np.concatenate([norm[0], norm[1]]), dtype=np.float64)
+        rc = lib().orc_decode_aug(arr, len(uniq), local_ids.ctypes.data, n, H, W, float(w0), float(lo), float(hi),
+                                  1 if clamp else 0, None if aff is None else aff.ctypes.data,
+                                  None if nrm is None else nrm.ctypes.data, out.ctypes.data, int(n_threads))
+    else:
+        rc = lib().orc_decode(arr, len(uniq), local_ids.ctypes.data, n, H, W, float(w0), float(lo), float(hi),
+                              1 if clamp else 0, out.ctypes.data, out8.ctypes.data if want_u8 else None,
+                              int(n_threads))
     if rc != 0:
         raise ValueError("orc_decode rejected its arguments")
     return (out, out8) if want_u8 else out

@@ -260,3 +260,75 @@ def test_thread_count_does_not_change_result():
     w = synth.workload(2, n_images=9, H=8, W=8)
     assert np.array_equal(oracle.decode(w.models, w.image_ids, 8, 8, n_threads=1),
                           oracle.decode(w.models, w.image_ids, 8, 8, n_threads=4))
+
+
+# ---- augmentation (Sec. III-B): affine map of the sampling grid + per-channel normalisation ---------------
+def _aug_models():
+    w = synth.workload(3, n_images=3, H=8, W=8)
+    ms = []
+    for m in w.models:      # spread the outputs over [0, 1] so the clamp and the normalisation both matter
+        last = m.layers[-1]
+        ms.append(Model(m.layers[:-1] + [Layer(last.n_in, last.n_out, 0, 0.0, 0, (last.weights * np.float32(120)).astype(np.float32),
+                                               last.keep, (last.bias + np.float32(0.5)).astype(np.float32))]))
+    return ms
+
+
+def test_aug_identity_is_plain_decode():
+    ms = _aug_models()
+    ids = np.array([2, 0, 1, 0])
+    ident = np.tile(np.array([1, 0, 0, 0, 1, 0], np.float64), (4, 1))
+    a = oracle.decode(ms, ids, 6, 9)
+    b = oracle.decode(ms, ids, 6, 9, affine=ident, norm=(np.ones(3), np.zeros(3)))
+    assert np.array_equal(a, b)
+
+
+def test_aug_flip_rotate_and_crop_against_plain_decode():
+    ms = _aug_models()
+    ids = np.array([0, 1, 2])
+    n, S = 3, 8
+    plain = oracle.decode(ms, ids, S, S, clamp=False)
+    flip = np.tile(np.array([-1, 0, 0, 0, 1, 0], np.float64), (n, 1))          # x -> -x: mirrored columns
+    assert np.allclose(oracle.decode(ms, ids, S, S, clamp=False, affine=flip), plain[:, :, :, ::-1], rtol=0, atol=1e-12)
+    vflip = np.tile(np.array([1, 0, 0, 0, -1, 0], np.float64), (n, 1))         # y -> -y: mirrored rows
+    assert np.allclose(oracle.decode(ms, ids, S, S, clamp=False, affine=vflip), plain[:, :, ::-1, :], rtol=0, atol=1e-12)
+    rot = np.tile(np.array([0, -1, 0, 1, 0, 0], np.float64), (n, 1))           # (x', y') = (-y, x)
+    got = oracle.decode(ms, ids, S, S, clamp=False, affine=rot)
+    want = np.transpose(plain, (0, 1, 3, 2))[:, :, ::-1, :]                     # out[i][j] = plain[j][S-1-i]
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+    # crop + resize: the top-left quadrant at full resolution == that quadrant of a plain 2x decode
+    crop = np.tile(np.array([0.5, 0, -0.5, 0, 0.5, -0.5], np.float64), (n, 1))
+    big = oracle.decode(ms, ids, 2 * S, 2 * S, clamp=False)
+    assert np.allclose(oracle.decode(ms, ids, S, S, clamp=False, affine=crop), big[:, :, :S, :S], rtol=0, atol=1e-12)
+    # translation by one pixel pitch of the base grid shifts columns by one
+    shift = np.tile(np.array([1, 0, 2.0 / S, 0, 1, 0], np.float64), (n, 1))
+    assert np.allclose(oracle.decode(ms, ids, S, S, clamp=False, affine=shift)[:, :, :, :-1], plain[:, :, :, 1:], rtol=0, atol=1e-12)
+    # per-slot maps are per slot: slot 1 flipped only
+    mixed = np.tile(np.array([1, 0, 0, 0, 1, 0], np.float64), (n, 1)); mixed[1] = flip[1]
+    got = oracle.decode(ms, ids, S, S, clamp=False, affine=mixed)
+    assert np.array_equal(got[0], plain[0]) and np.array_equal(got[2], plain[2])
+    assert np.allclose(got[1], plain[1][:, :, ::-1], rtol=0, atol=1e-12)
+
+
+def test_aug_normalisation_is_per_channel_after_clamp():
+    ms = _aug_models()
+    ids = np.array([1, 2])
+    plain = oracle.decode(ms, ids, 7, 5)                       # clamped
+    assert (plain == 0).any() and (plain == 1).any()
+    scale, shift = np.array([4.0, 0.5, -2.0]), np.array([-1.5, 0.25, 3.0])
+    got = oracle.decode(ms, ids, 7, 5, norm=(scale, shift))
+    want = plain * scale[None, :, None, None] + shift[None, :, None, None]
+    assert np.allclose(got, want, rtol=0, atol=1e-15)
+    raw = oracle.decode(ms, ids, 7, 5, clamp=False)
+    got_raw = oracle.decode(ms, ids, 7, 5, clamp=False, norm=(scale, shift))
+    assert np.allclose(got_raw, raw * scale[None, :, None, None] + shift[None, :, None, None], rtol=0, atol=1e-14)
+
+
+def test_aug_c_and_numpy_oracles_agree():
+    ms = _aug_models()
+    rng = np.random.default_rng(8)
+    ids = np.array([0, 2, 1, 1])
+    aff = rng.uniform(-1.2, 1.2, (4, 6))
+    nrm = (rng.uniform(0.5, 5, 3), rng.uniform(-2, 2, 3))
+    a = oracle.decode(ms, ids, 6, 7, affine=aff, norm=nrm)
+    b = oracle_np.decode(ms, ids, 6, 7, affine=aff, norm=nrm)
+    assert np.abs(a - b).max() < 1e-12
