@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
     ap.add_argument("--fp32-mfma", action="store_true", help="time the fp32 MFMA kernels instead of the default split-precision path")
+    ap.add_argument("--augment", action="store_true",
+                    help="time the decode with a per-slot affine map of the sampling grid and per-channel "
+                         "normalisation fused in (fp32 output only)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="run only a plain device-to-device copy of MIB MiB per step (counter calibration) and exit")
     args = ap.parse_args()
@@ -96,10 +99,20 @@ def main() -> int:
     out = torch.empty((n, 3, H, W), dtype=torch.float32, device="cuda")
     out8 = torch.empty((n, 3, H, W), dtype=torch.uint8, device="cuda") if w.out_u8 else None
     dtype = rinr.OUT_F32_AND_U8 if w.out_u8 else rinr.OUT_F32
+    affine, norm = None, None
+    if args.augment:                    # flips, small rotations, zoom and shifts; ImageNet-style normalisation
+        rng = np.random.default_rng(0)
+        th, z = rng.uniform(-0.5, 0.5, n), rng.uniform(0.6, 1.2, n)
+        fx = np.where(rng.uniform(size=n) < 0.5, -1.0, 1.0)
+        aff = np.stack([fx * z * np.cos(th), -z * np.sin(th), rng.uniform(-.25, .25, n),
+                        fx * z * np.sin(th), z * np.cos(th), rng.uniform(-.25, .25, n)], axis=1).astype(np.float32)
+        affine = torch.from_numpy(aff).cuda()
+        norm = ((1 / 0.229, 1 / 0.224, 1 / 0.225), (-0.485 / 0.229, -0.456 / 0.224, -0.406 / 0.225))
+        dtype, out8 = rinr.OUT_F32, None
 
     def timed(flags):
         def step():
-            st.decode_batch_ex(ids, H, W, dtype, flags, out=out, out_u8=out8)
+            st.decode_batch_ex(ids, H, W, dtype, flags, out=out, out_u8=out8, affine=affine, norm=norm)
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
@@ -160,7 +173,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype_name, "data": "synthetic",
         "config": {"workload": w.name, "images": n, "H": H, "W": W,
-                   "outputs": "fp32+uint8 NCHW" if w.out_u8 else "fp32 NCHW",
+                   "outputs": "fp32+uint8 NCHW" if (w.out_u8 and not args.augment) else "fp32 NCHW",
+                   "augmentation": "per-slot affine grid map + per-channel normalisation" if args.augment else "none",
                    "flop_per_pixel_mean": float(flop_px.mean()), "alu_ops_per_pixel_mean": float(alu_px.mean()),
                    "launch": info},
         "roofline": roof,

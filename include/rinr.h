@@ -119,14 +119,26 @@ enum { RINR_OUT_F32 = 1,           /* out: float [n][3][H][W], clamp(y, 0, 1)   
        RINR_OUT_U8 = 2,            /* out: uint8 [n][3][H][W], rint(255 * clamp(y, 0, 1))     */
        RINR_OUT_F32_AND_U8 = 3 };  /* out: float tensor, opts.out_u8: uint8 tensor            */
 enum { RINR_FLAG_NO_CLAMP = 1,     /* fp32 output only: write the linear output unclamped     */
-       RINR_FLAG_FP32_MFMA = 2 };  /* run the layers on fp32 MFMA instead of the default
+       RINR_FLAG_FP32_MFMA = 2,    /* run the layers on fp32 MFMA instead of the default
                                       split-precision fp16 MFMA (hi+lo operand pairs, fp32
                                       accumulate); same results within the stated tolerance  */
+       RINR_FLAG_NORMALIZE = 4 };  /* fp32 output only: out = value * norm_scale[c] + norm_shift[c]
+                                      per channel c, after the clamp                          */
 
+/* Augmentation on the GPU, fused into the decode (Sec. III-B: decoded images are augmented
+ * on the GPU before they reach the backbone).  Geometric augmentation (flip, crop + resize,
+ * rotation, translation, zoom) is a per-slot affine map of the sampling grid, free for a
+ * resolution-free decode:  (x', y') = (A[0] x + A[1] y + A[2],  A[3] x + A[4] y + A[5])
+ * with (x, y) the pixel-centre coordinate of the H x W grid; the MLP is evaluated at (x', y').
+ * Photometric normalisation is RINR_FLAG_NORMALIZE. */
 typedef struct {
     int32_t out_dtype;       /* RINR_OUT_*                                              */
     int32_t flags;           /* RINR_FLAG_*                                             */
     void *out_u8;            /* device; second output for RINR_OUT_F32_AND_U8, else NULL */
+    const float *affine;     /* device; float[n][6], one 2x3 map per slot, or NULL = identity.
+                                Mapped coordinates must stay below 6e4 in magnitude.       */
+    float norm_scale[3];     /* used with RINR_FLAG_NORMALIZE, e.g. 1/std per channel      */
+    float norm_shift[3];     /* used with RINR_FLAG_NORMALIZE, e.g. -mean/std per channel  */
 } rinr_decode_opts;
 
 /* Decodes slots s = 0..n-1 (Sec. III-B: batch select + pixel- and image-parallel
@@ -136,15 +148,16 @@ typedef struct {
  * stream: a hipStream_t (NULL = the default stream).  Asynchronous: enqueues kernels
  * on `stream` and returns; never synchronises, never reads the host copy of the blob.
  * n == 0 is OK and launches nothing.  Host-detectable errors (NULL, n < 0, H or W <= 0,
- * n*3*H*W overflowing int64 / a plane >= 2^31 pixels, misaligned out, bad out_dtype,
- * NO_CLAMP with a uint8 output) are returned before anything is enqueued.  An id outside
+ * n*3*H*W overflowing int64 / a plane >= 2^31 pixels, misaligned out or affine, bad out_dtype,
+ * NO_CLAMP or NORMALIZE with a uint8 output, non-finite norm values) are returned before
+ * anything is enqueued.  An id outside
  * [0, n_models) cannot be seen from the host: that slot is written as zeros and a sticky
  * device counter is incremented (read it with rinr_store_status).
  * Domain: every sine argument w0*(Wx+b) must stay within +-512*pi (the hardware sine's
  * range; sine networks stay within a few tens of radians).  The default split-precision
  * kernels also need |w * w0/2pi| and the coordinate bounds below 6e4 (fp16 range); a store
  * that breaks this is served by the fp32 MFMA kernels automatically.
- * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL}. */
+ * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL, NULL}. */
 int rinr_decode_batch(const rinr_store *models, const int64_t *image_ids, int32_t n,
                       int32_t H, int32_t W, void *out, void *stream);
 int rinr_decode_batch_ex(const rinr_store *models, const int64_t *image_ids, int32_t n,

@@ -260,7 +260,11 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (n < 0 || H <= 0 || W <= 0) return RINR_E_ARG;
     const int dt = opts->out_dtype;
     if (dt != RINR_OUT_F32 && dt != RINR_OUT_U8 && dt != RINR_OUT_F32_AND_U8) return RINR_E_ARG;
-    if (opts->flags & ~(RINR_FLAG_NO_CLAMP | RINR_FLAG_FP32_MFMA)) return RINR_E_ARG;
+    if (opts->flags & ~(RINR_FLAG_NO_CLAMP | RINR_FLAG_FP32_MFMA | RINR_FLAG_NORMALIZE)) return RINR_E_ARG;
+    if ((opts->flags & RINR_FLAG_NORMALIZE) && dt != RINR_OUT_F32) return RINR_E_ARG;
+    if (opts->flags & RINR_FLAG_NORMALIZE)
+        for (int c = 0; c < 3; ++c)
+            if (!std::isfinite(opts->norm_scale[c]) || !std::isfinite(opts->norm_shift[c])) return RINR_E_ARG;
     if ((opts->flags & RINR_FLAG_NO_CLAMP) && dt != RINR_OUT_F32) return RINR_E_ARG;
     const int64_t HW = (int64_t)H * W;
     if (HW >= (int64_t)1 << 31) return RINR_E_SIZE;
@@ -270,6 +274,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (dt == RINR_OUT_F32_AND_U8 && !opts->out_u8) return RINR_E_NULL;
     if (dt != RINR_OUT_U8 && ((uintptr_t)out & 3)) return RINR_E_ALIGN;
     if ((uintptr_t)image_ids & 7) return RINR_E_ALIGN;
+    if ((uintptr_t)opts->affine & 3) return RINR_E_ALIGN;
 
     const StoreHeader &h = s->sum.header;
     DecodeArgs a;
@@ -295,6 +300,12 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     a.pre = (float)((double)h.w0 / (2.0 * M_PI));
     a.no_clamp = (opts->flags & RINR_FLAG_NO_CLAMP) ? 1u : 0u;
     a.neg1 = -1.0f;
+    a.affine = opts->affine;
+    a.normalize = (opts->flags & RINR_FLAG_NORMALIZE) ? 1u : 0u;
+    for (int c = 0; c < 3; ++c) {
+        a.ns[c] = a.normalize ? opts->norm_scale[c] : 1.0f;
+        a.nb[c] = a.normalize ? opts->norm_shift[c] : 0.0f;
+    }
     const bool xdl = s->xdl_ok && !(opts->flags & RINR_FLAG_FP32_MFMA) && !g_force_fp32;
 
     const uint32_t tiles = (uint32_t)((HW + 63) >> 6);
@@ -346,9 +357,8 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
 extern "C" int rinr_decode_batch(const rinr_store *s, const int64_t *image_ids, int32_t n, int32_t H, int32_t W,
                                  void *out, void *stream) {
     rinr_decode_opts o;
+    std::memset(&o, 0, sizeof o);
     o.out_dtype = RINR_OUT_F32;
-    o.flags = 0;
-    o.out_u8 = nullptr;
     return rinr_decode_batch_ex(s, image_ids, n, H, W, out, &o, stream);
 }
 

@@ -202,6 +202,9 @@ struct DecodeArgs {
     uint32_t no_clamp;
     uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
     float neg1;                   // -1.0f, passed as data (keeps a subtraction in mixed-precision fma form)
+    const float *affine;          // per-slot 2x3 map of the sampling grid, or NULL
+    float ns[3], nb[3];           // per-channel scale / shift applied after the clamp when normalize != 0
+    uint32_t normalize;
 };
 
 // sin(2 pi r): the hardware sine takes its argument in revolutions and reduces the range
@@ -266,6 +269,9 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
     const float *wfirst = lds + LY::off_first() + lane * MTS;
     const float *wout = lds + LY::off_out(L) + g * KSTEPS * 4;
     const float ob0 = lds[LY::off_outb(L) + 0], ob1 = lds[LY::off_outb(L) + 1], ob2 = lds[LY::off_outb(L) + 2];
+    float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
+    if (a.affine)
+        for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)slot * 6 + q];
 
     for (uint32_t tile = tile0 + wave; tile < tile1;) {
         float Bv[NT][KSTEPS];
@@ -279,7 +285,8 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
             const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
             const float x = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
             const float y = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
-            bx[nt] = g == 0 ? x : (g == 1 ? y : 0.0f);
+            const float xa = fmaf(af[0], x, fmaf(af[1], y, af[2])), ya = fmaf(af[3], x, fmaf(af[4], y, af[5]));
+            bx[nt] = g == 0 ? xa : (g == 1 ? ya : 0.0f);
         }
         // ---- first layer 2 -> width: one k-step, bias as the C operand
         {
@@ -363,6 +370,11 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
             r0 = fminf(fmaxf(r0, 0.0f), 1.0f);
             r1 = fminf(fmaxf(r1, 0.0f), 1.0f);
             r2 = fminf(fmaxf(r2, 0.0f), 1.0f);
+        }
+        if (a.normalize) {
+            r0 = fmaf(r0, a.ns[0], a.nb[0]);
+            r1 = fmaf(r1, a.ns[1], a.nb[1]);
+            r2 = fmaf(r2, a.ns[2], a.nb[2]);
         }
         const uint32_t p = (tile << 6) + lane;
         if (p < a.HW) {

@@ -305,6 +305,11 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
     const XLayer *tab = (const XLayer *)lds;
     const float neg1 = a.neg1;
     const XLayer e0 = tab[0], eo = tab[L - 1];
+    float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
+    if (a.affine)
+        for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)slot * 6 + q];
+    const float nsc = g == 0 ? a.ns[0] : (g == 1 ? a.ns[1] : a.ns[2]);     // lane group g stores channel g
+    const float nsh = g == 0 ? a.nb[0] : (g == 1 ? a.nb[1] : a.nb[2]);
 
     for (uint32_t tile = tile0 + wave; tile < tile1;) {
         XHalf<MT> X, Y;
@@ -318,8 +323,9 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
                 uint32_t p = (tile << 6) + nt * 16 + n;
                 p = min(p, a.HW - 1);
                 const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
-                const float x = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
-                const float y = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+                const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
+                const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+                const float x = fmaf(af[0], x0, fmaf(af[1], y0, af[2])), y = fmaf(af[3], x0, fmaf(af[4], y0, af[5]));
                 const _Float16 xh = (_Float16)x, yh = (_Float16)y;
                 const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
                 const _Float16 z = (_Float16)0.0f;
@@ -396,6 +402,7 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
             for (int nt = 0; nt < 4; ++nt) {
                 float r = O[nt][0];
                 if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
+                if (a.normalize) r = fmaf(r, nsc, nsh);
                 const uint32_t p = (tile << 6) + nt * 16 + n;
                 if (g < 3 && p < a.HW) {
                     const size_t at = plane0 + (size_t)g * a.HW + p;

@@ -19,6 +19,7 @@ OK = 0
 OUT_F32, OUT_U8, OUT_F32_AND_U8 = 1, 2, 3
 FLAG_NO_CLAMP = 1
 FLAG_FP32_MFMA = 2
+FLAG_NORMALIZE = 4
 E_NULL, E_ARG, E_MODEL, E_SIZE, E_FORMAT, E_UNSUPPORTED, E_ALIGN, E_HIP = -1, -2, -3, -4, -5, -6, -7, -8
 
 EXPORTS = ["rinr_pack_size", "rinr_pack", "rinr_unpack_layer", "rinr_store_open", "rinr_store_close",
@@ -41,7 +42,8 @@ class StoreOpts(C.Structure):
 
 
 class DecodeOpts(C.Structure):
-    _fields_ = [("out_dtype", C.c_int32), ("flags", C.c_int32), ("out_u8", C.c_void_p)]
+    _fields_ = [("out_dtype", C.c_int32), ("flags", C.c_int32), ("out_u8", C.c_void_p), ("affine", C.c_void_p),
+                ("norm_scale", C.c_float * 3), ("norm_shift", C.c_float * 3)]
 
 
 class RinrError(RuntimeError):
@@ -218,8 +220,11 @@ class Store:
         return out
 
     def decode_batch_ex(self, image_ids, H: int, W: int, out_dtype: int = OUT_F32, flags: int = 0,
-                        out=None, out_u8=None, stream=None):
-        """rinr_decode_batch_ex.  Returns out (and out_u8 for OUT_F32_AND_U8)."""
+                        out=None, out_u8=None, stream=None, affine=None, norm=None):
+        """rinr_decode_batch_ex.  Returns out (and out_u8 for OUT_F32_AND_U8).
+
+        affine: float32 CUDA tensor [n, 6] (per-slot map of the sampling grid) or None;
+        norm: (scale[3], shift[3]) host numbers, sets FLAG_NORMALIZE."""
         torch = self._torch
         n = int(image_ids.numel())
         if out is None:
@@ -228,6 +233,13 @@ class Store:
         if out_dtype == OUT_F32_AND_U8 and out_u8 is None:
             out_u8 = torch.empty((n, 3, H, W), dtype=torch.uint8, device=self.device)
         o = DecodeOpts(out_dtype, flags, out_u8.data_ptr() if (out_u8 is not None and n) else None)
+        if affine is not None:
+            assert affine.dtype == torch.float32 and affine.is_contiguous() and tuple(affine.shape) == (n, 6)
+            o.affine = affine.data_ptr() if n else None
+        if norm is not None:
+            o.flags |= FLAG_NORMALIZE
+            o.norm_scale = (C.c_float * 3)(*[float(v) for v in norm[0]])
+            o.norm_shift = (C.c_float * 3)(*[float(v) for v in norm[1]])
         _check(lib().rinr_decode_batch_ex(self._h, image_ids.data_ptr() if n else None, n, H, W,
                                           out.data_ptr() if n else None, C.byref(o), _stream_ptr(stream)),
                "rinr_decode_batch_ex")

@@ -1,0 +1,113 @@
+"""GPU parity of the fused augmentation (per-slot affine map of the sampling grid + per-channel
+normalisation, paper Sec. III-B) against the fp64 oracle, through the C ABI, in both matrix modes."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_2306_16699_amd import rinr, synth
+from paper_2306_16699_amd.synth import Layer, Model
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+
+
+def image_like(models, gain=40.0):
+    out = []
+    for m in models:
+        last = m.layers[-1]
+        out.append(Model(m.layers[:-1] + [Layer(last.n_in, last.n_out, 0, 0.0, 0, (last.weights * np.float32(gain)).astype(np.float32),
+                                                last.keep, (last.bias + np.float32(0.5)).astype(np.float32))]))
+    return out
+
+
+def random_affines(rng, n):
+    """Flips, rotations up to 30 degrees, zoom 0.6..1.2 and shifts up to 0.25: what a training pipeline draws."""
+    a = np.zeros((n, 6), np.float32)
+    for s in range(n):
+        th = rng.uniform(-np.pi / 6, np.pi / 6)
+        z = rng.uniform(0.6, 1.2)
+        fx = -1.0 if rng.uniform() < 0.5 else 1.0
+        a[s] = [fx * z * np.cos(th), -z * np.sin(th), rng.uniform(-.25, .25), fx * z * np.sin(th), z * np.cos(th), rng.uniform(-.25, .25)]
+    return a
+
+
+@pytest.mark.parametrize("k,n,H,W", [(2, 40, 32, 32), (3, 12, 45, 52), (4, 5, 75, 53), (5, 48, 33, 40), (1, 16, 32, 32)])
+def test_augmented_decode_matches_oracle(k, n, H, W):
+    import torch
+    w = synth.workload(k, n_images=n, pool=200, H=H, W=W)
+    models = image_like(w.models)
+    rng = np.random.default_rng(k)
+    aff = random_affines(rng, w.n)
+    norm = (np.array([1 / 0.229, 1 / 0.224, 1 / 0.225], np.float32), np.array([-0.485 / 0.229, -0.456 / 0.224, -0.406 / 0.225], np.float32))
+    st = rinr.Store(rinr.pack(models))
+    ids = torch.from_numpy(w.image_ids).cuda()
+    aff_d = torch.from_numpy(aff).cuda()
+    ref = oracle.decode(models, w.image_ids, H, W, affine=aff.astype(np.float64), norm=(norm[0].astype(np.float64), norm[1].astype(np.float64)))
+    ref_geo = oracle.decode(models, w.image_ids, H, W, affine=aff.astype(np.float64), clamp=False)
+    tol_n = TOL * float(np.abs(norm[0]).max())          # the normalisation scales the error with the value
+    for mode in (0, rinr.FLAG_FP32_MFMA):
+        got = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode, affine=aff_d, norm=norm).cpu().numpy()
+        assert np.abs(got - ref).max() <= tol_n, (mode, np.abs(got - ref).max())
+        geo = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP, affine=aff_d).cpu().numpy()
+        assert np.abs(geo - ref_geo).max() <= TOL, (mode, np.abs(geo - ref_geo).max())
+        # uint8 output with a geometric map only (normalisation is fp32-only)
+        f32, u8 = st.decode_batch_ex(ids, H, W, rinr.OUT_F32_AND_U8, mode, affine=aff_d)
+        assert np.array_equal(u8.cpu().numpy(), np.rint(255.0 * f32.cpu().numpy()).astype(np.uint8))
+        assert np.abs(f32.cpu().numpy() - np.clip(ref_geo, 0, 1)).max() <= TOL
+    assert st.status() == 0
+    st.close()
+
+
+def test_identity_map_and_unit_normalisation_change_nothing():
+    import torch
+    w = synth.workload(3, n_images=6, H=20, W=27)
+    st = rinr.Store(rinr.pack(image_like(w.models)))
+    ids = torch.from_numpy(w.image_ids).cuda()
+    ident = torch.tensor([[1, 0, 0, 0, 1, 0]] * 6, dtype=torch.float32, device="cuda")
+    for mode in (0, rinr.FLAG_FP32_MFMA):
+        a = st.decode_batch_ex(ids, 20, 27, rinr.OUT_F32, mode).cpu().numpy()
+        b = st.decode_batch_ex(ids, 20, 27, rinr.OUT_F32, mode, affine=ident, norm=((1, 1, 1), (0, 0, 0))).cpu().numpy()
+        assert np.array_equal(a, b)
+    st.close()
+
+
+def test_flip_and_crop_on_the_gpu():
+    """The same geometric facts that pin the oracle, checked on the GPU path against its own plain decode."""
+    import torch
+    w = synth.workload(2, n_images=4, H=16, W=16)
+    st = rinr.Store(rinr.pack(image_like(w.models)))
+    ids = torch.from_numpy(w.image_ids).cuda()
+    plain = st.decode_batch_ex(ids, 16, 16, rinr.OUT_F32, rinr.FLAG_NO_CLAMP).cpu().numpy()
+    flip = torch.tensor([[-1, 0, 0, 0, 1, 0]] * 4, dtype=torch.float32, device="cuda")
+    got = st.decode_batch_ex(ids, 16, 16, rinr.OUT_F32, rinr.FLAG_NO_CLAMP, affine=flip).cpu().numpy()
+    assert np.abs(got - plain[:, :, :, ::-1]).max() < 2e-4
+    crop = torch.tensor([[0.5, 0, -0.5, 0, 0.5, -0.5]] * 4, dtype=torch.float32, device="cuda")
+    big = st.decode_batch_ex(ids, 32, 32, rinr.OUT_F32, rinr.FLAG_NO_CLAMP).cpu().numpy()
+    got = st.decode_batch_ex(ids, 16, 16, rinr.OUT_F32, rinr.FLAG_NO_CLAMP, affine=crop).cpu().numpy()
+    assert np.abs(got - big[:, :, :16, :16]).max() < 2e-4
+    st.close()
+
+
+def test_augmentation_argument_errors():
+    import torch
+    w = synth.workload(2, n_images=2)
+    st = rinr.Store(rinr.pack(w.models))
+    L = rinr.lib()
+    ids = torch.from_numpy(w.image_ids).cuda()
+    out = torch.empty((2, 3, 4, 4), device="cuda")
+    aff = torch.zeros((2, 6), device="cuda")
+    o = rinr.DecodeOpts(rinr.OUT_U8, rinr.FLAG_NORMALIZE, None)
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ARG
+    o = rinr.DecodeOpts(rinr.OUT_F32_AND_U8, rinr.FLAG_NORMALIZE, out.data_ptr())
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ARG
+    o = rinr.DecodeOpts(rinr.OUT_F32, rinr.FLAG_NORMALIZE, None)
+    o.norm_scale = (C.c_float * 3)(1.0, float("nan"), 1.0)
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ARG
+    o = rinr.DecodeOpts(rinr.OUT_F32, 0, None)
+    o.affine = aff.data_ptr() + 2
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ALIGN
+    o = rinr.DecodeOpts(rinr.OUT_F32, 8, None)
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ARG
+    st.close()
