@@ -58,9 +58,9 @@ ClassImpl impl_for(uint32_t cls, int tile_rows_wide) {
 }
 
 // How many workgroups share one slot's pixels.  Every workgroup pays one expand of the model
-// (not overlapped with compute when only one workgroup fits a CU), and the grid runs in rounds
-// of n_cu * resident workgroups, so both very many small workgroups and a last, mostly empty
-// round cost time.  Pick the split that minimises a simple model of both.
+// (not overlapped with compute when only one workgroup fits a CU), and a grid that does not
+// fill the machine evenly ends in a tail, so both very many small workgroups and few large
+// ones cost time.  Pick the split that minimises a simple model of both.
 struct Plan { uint32_t chunks, tiles_per_chunk; };
 Plan plan_chunks(double n_slots, uint32_t tiles, uint32_t nw, int n_cu, int resident, double tile_us) {
     const double expand_us = 15.0;
@@ -84,10 +84,14 @@ Plan plan_chunks(double n_slots, uint32_t tiles, uint32_t nw, int n_cu, int resi
         double r_eff = blocks / n_cu;
         if (r_eff > resident) r_eff = resident;
         if (r_eff < 1.0) r_eff = 1.0;
-        const double rounds = std::ceil(blocks / (n_cu * r_eff) - 1e-9);
-        const double round_us = tpc * r_eff / 4.0 * tile_us + (r_eff > 1.5 ? expand_us / r_eff : expand_us);
-        const double t = rounds * round_us;
-        if (t < best_t * 0.995) { best_t = t; best = Plan{cc, tpc}; }
+        // a workgroup's duration with r_eff of them sharing a CU's four SIMDs; the expand hides behind
+        // the other resident workgroups when there are any
+        const double block_us = tpc * r_eff / 4.0 * tile_us + (r_eff > 1.5 ? expand_us / r_eff : expand_us);
+        const double par = n_cu * r_eff;
+        // all workgroups in flight at once: one duration; otherwise the work spread over the machine
+        // plus, on average, half a workgroup of tail
+        const double t = blocks <= par ? block_us : blocks * block_us / par + 0.5 * block_us;
+        if (t < best_t * 0.95) { best_t = t; best = Plan{cc, tpc}; }     // finer splits must pay for their extra expands clearly
         if (tpc <= nw) break;
     }
     return best;
@@ -224,6 +228,12 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
             return RINR_E_HIP;
         }
     }
+    if (hip_fail(hipFuncSetAttribute((const void *)decode_xdl_any_kernel<kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+        hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<16, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+        hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<32, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
+        delete s;
+        return RINR_E_HIP;
+    }
     if (hip_fail(hipGetDevice(&s->device))) { delete s; return RINR_E_HIP; }
     hipDeviceProp_t prop;
     if (hip_fail(hipGetDeviceProperties(&prop, s->device))) { delete s; return RINR_E_HIP; }
@@ -314,37 +324,68 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
 
     const int knob = g_blocks_per_cu * 2 + (xdl ? 1 : 0);
     const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads && s->plan_knob == knob);
+    for (uint32_t c = 1; c <= kMaxClass; ++c) a.stage_off[c] = xdl ? s->xdl_stage_off[c] : s->stage_off[c];
+    int n_classes = 0;
+    for (uint32_t c = 1; c <= kMaxClass; ++c) n_classes += s->sum.class_count[c] ? 1 : 0;
+
     int launches = 0;
-    bool first = true;
     uint32_t big_lds = 0, total_blocks = 0;
-    for (uint32_t c = 1; c <= kMaxClass; ++c) {
-        if (!s->sum.class_count[c]) continue;
-        const ClassImpl im = impl_for(c, s->tile_rows_wide);
+    if (n_classes > 1) {
+        // ragged store: one grid over all slots, each workgroup runs the body of its slot's class
+        const void *fn = xdl ? (const void *)decode_xdl_any_kernel<kThreads>
+                             : (s->tile_rows_wide == 32 ? (const void *)decode_any_kernel<32, kThreads>
+                                                        : (const void *)decode_any_kernel<16, kThreads>);
+        uint32_t lds_bytes = 0;
+        double tile_us = 0.0;
+        for (uint32_t c = 1; c <= kMaxClass; ++c) {
+            if (!s->sum.class_count[c]) continue;
+            lds_bytes = std::max(lds_bytes, xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c]);
+            tile_us += (xdl ? s->class_tile_us_xdl[c] : s->class_tile_us[c]) * (double)s->sum.class_count[c] /
+                       (double)h.n_models;
+        }
         if (replan) {
             int resident = 1;
-            if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)(xdl ? im.decode_xdl : im.decode),
-                                                                      threads, xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c])) ||
-                resident < 1)
+            if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, fn, threads, lds_bytes)) || resident < 1)
                 resident = 1;
-            // expected slots of this class in the batch, if ids are spread like the store's models
-            const double share = (double)s->sum.class_count[c] / (double)(h.n_models ? h.n_models : 1);
-            s->plan[c] = plan_chunks(share * n, tiles, nw, s->n_cu, resident, xdl ? s->class_tile_us_xdl[c] : s->class_tile_us[c]);
+            s->plan[0] = plan_chunks((double)n, tiles, nw, s->n_cu, resident, tile_us);
         }
-        const Plan pl = s->plan[c];
+        const Plan pl = s->plan[0];
         if ((uint64_t)n * pl.chunks > 0x7FFFFFFFull) return RINR_E_SIZE;
         a.chunks = pl.chunks;
         a.tiles_per_chunk = pl.tiles_per_chunk;
-        a.cls = c;
-        a.stage_off = xdl ? s->xdl_stage_off[c] : s->stage_off[c];
-        a.handle_bad = first ? 1u : 0u;
-        first = false;
-        const uint32_t lds_bytes = xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c];
-        hipLaunchKernelGGL(xdl ? im.decode_xdl : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
-                           (hipStream_t)stream, a);
-        RINR_HIP(hipGetLastError());
-        ++launches;
-        total_blocks += (uint32_t)n * pl.chunks;
+        a.cls = 0;
+        a.handle_bad = 1u;
+        void *kargs[] = {(void *)&a};
+        RINR_HIP(hipLaunchKernel(fn, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), kargs, lds_bytes,
+                                 (hipStream_t)stream));
+        launches = 1;
+        total_blocks = (uint32_t)n * pl.chunks;
         big_lds = lds_bytes;
+    } else {
+        for (uint32_t c = 1; c <= kMaxClass; ++c) {
+            if (!s->sum.class_count[c]) continue;
+            const ClassImpl im = impl_for(c, s->tile_rows_wide);
+            const uint32_t lds_bytes = xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c];
+            if (replan) {
+                int resident = 1;
+                if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)(xdl ? im.decode_xdl : im.decode),
+                                                                          threads, lds_bytes)) || resident < 1)
+                    resident = 1;
+                s->plan[c] = plan_chunks((double)n, tiles, nw, s->n_cu, resident, xdl ? s->class_tile_us_xdl[c] : s->class_tile_us[c]);
+            }
+            const Plan pl = s->plan[c];
+            if ((uint64_t)n * pl.chunks > 0x7FFFFFFFull) return RINR_E_SIZE;
+            a.chunks = pl.chunks;
+            a.tiles_per_chunk = pl.tiles_per_chunk;
+            a.cls = c;
+            a.handle_bad = 1u;
+            hipLaunchKernelGGL(xdl ? im.decode_xdl : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
+                               (hipStream_t)stream, a);
+            RINR_HIP(hipGetLastError());
+            launches = 1;
+            total_blocks = (uint32_t)n * pl.chunks;
+            big_lds = lds_bytes;
+        }
     }
     s->plan_hw = HW; s->plan_n = n; s->plan_threads = threads; s->plan_knob = knob;
     s->last_info[0] = launches;

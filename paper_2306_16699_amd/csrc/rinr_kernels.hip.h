@@ -197,8 +197,8 @@ struct DecodeArgs {
     float pre;                    // w0 / (2 pi)
     uint32_t chunks;              // workgroups per slot
     uint32_t tiles_per_chunk;     // 64-pixel tiles per workgroup
-    uint32_t stage_off;           // float offset of the record staging area in LDS
-    uint32_t cls;                 // width class this launch serves (padded width / 16)
+    uint32_t stage_off[5];        // per width class: float offset of the record staging area in LDS
+    uint32_t cls;                 // width class this launch serves (padded width / 16); 0 = every class
     uint32_t no_clamp;
     uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
     float neg1;                   // -1.0f, passed as data (keeps a subtraction in mixed-precision fma form)
@@ -215,43 +215,59 @@ __device__ __forceinline__ float sin_rev(float r) {
     return __builtin_amdgcn_sinf(r);
 }
 
-template <int TM, int WP, int NTHREADS>
-__global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
+// What one workgroup has to do: a range of 64-pixel tiles of one batch slot, and the slot's model.
+struct Work {
+    uint32_t slot, tile0, tile1;
+    size_t plane0;               // element offset of the slot's first output plane
+    IndexEntry e;
+    uint32_t cls;                // width class of the model
+};
+
+// ---- gather: workgroup -> (slot, tile range); slot -> id -> index entry (Sec. III-B batch select).
+// Returns false when the workgroup has nothing to decode: empty tile range, or an out-of-range id
+// (then the launch that handles bad ids has zero-filled the range and counted it), or a model of
+// another class than this launch serves.
+__device__ __forceinline__ bool decode_prologue(const DecodeArgs &a, Work &w) {
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    w.slot = blockIdx.x / a.chunks;
+    const uint32_t chunk = blockIdx.x - w.slot * a.chunks;
+    w.tile0 = chunk * a.tiles_per_chunk;
+    const uint32_t ntiles_img = (a.HW + 63) >> 6;
+    if (w.tile0 >= ntiles_img) return false;
+    w.tile1 = min(w.tile0 + a.tiles_per_chunk, ntiles_img);
+    w.plane0 = (size_t)w.slot * 3 * a.HW;
+    const int64_t id = a.ids[w.slot];
+    if (id < 0 || (uint64_t)id >= a.n_models) {
+        if (!a.handle_bad) return false;
+        const uint32_t p0 = w.tile0 << 6, p1 = min(w.tile1 << 6, a.HW);
+        for (int c = 0; c < 3; ++c)
+            for (uint32_t p = p0 + tid; p < p1; p += nthreads) {
+                if (a.out_f32) a.out_f32[w.plane0 + (size_t)c * a.HW + p] = 0.0f;
+                if (a.out_u8) a.out_u8[w.plane0 + (size_t)c * a.HW + p] = 0;
+            }
+        if (chunk == 0 && tid == 0) atomicAdd(a.status, 1ull);
+        return false;
+    }
+    w.e = *(const IndexEntry *)(a.blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
+    w.cls = w.e.width == 0 ? 1u : (w.e.width + 15u) >> 4;
+    return a.cls == 0 || w.cls == a.cls;
+}
+
+template <int TM, int WP>
+__device__ __forceinline__ void decode_body(const DecodeArgs &a, const Work &w, float *lds) {
     typedef Layout<TM, WP> LY;
     typedef Tile<TM> T;
     typedef typename T::acc_t acc_t;
     constexpr int G = LY::G, RV = LY::RV, MT = LY::MT, MTS = LY::MTS, KSTEPS = LY::KSTEPS;
     constexpr int NT = G;                      // pixel tiles per wavefront: NT * TM = 64 pixels
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const uint32_t slot = blockIdx.x / a.chunks, chunk = blockIdx.x - slot * a.chunks;
-    const uint32_t tile0 = chunk * a.tiles_per_chunk;
-    const uint32_t ntiles_img = (a.HW + 63) >> 6;
-    if (tile0 >= ntiles_img) return;
-    const uint32_t tile1 = min(tile0 + a.tiles_per_chunk, ntiles_img);
-    const size_t plane0 = (size_t)slot * 3 * a.HW;
-
-    // ---- gather: slot -> id -> index entry (Sec. III-B batch select)
-    const int64_t id = a.ids[slot];
-    if (id < 0 || (uint64_t)id >= a.n_models) {
-        if (!a.handle_bad) return;
-        const uint32_t p0 = tile0 << 6, p1 = min(tile1 << 6, a.HW);
-        for (int c = 0; c < 3; ++c)
-            for (uint32_t p = p0 + tid; p < p1; p += nthreads) {
-                if (a.out_f32) a.out_f32[plane0 + (size_t)c * a.HW + p] = 0.0f;
-                if (a.out_u8) a.out_u8[plane0 + (size_t)c * a.HW + p] = 0;
-            }
-        if (chunk == 0 && tid == 0) atomicAdd(a.status, 1ull);
-        return;
-    }
-    const IndexEntry e = *(const IndexEntry *)(a.blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
-    const uint32_t cls = e.width == 0 ? 1u : (e.width + 15u) >> 4;
-    if (cls != a.cls) return;
+    const uint32_t slot = w.slot, tile0 = w.tile0, tile1 = w.tile1;
+    const size_t plane0 = w.plane0;
+    const IndexEntry e = w.e;
     const int L = e.n_layers;
 
     // ---- stage the packed record, expand it
-    uint32_t *stage = (uint32_t *)(lds + a.stage_off);
+    uint32_t *stage = (uint32_t *)(lds + a.stage_off[WP / 16]);
     {
         const uint4 *src = (const uint4 *)(a.blob + e.off);
         uint4 *dst = (uint4 *)stage;
@@ -392,6 +408,30 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
         uint32_t nt_ = 0;
         if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
         tile = __builtin_amdgcn_readfirstlane(nt_);
+    }
+}
+
+// One width class per launch (a.cls != 0), or every class in one launch (a.cls == 0; TMW = MFMA
+// tile rows for padded widths 32 and 64): a ragged batch then runs as one grid instead of one
+// partly filled grid per class.
+template <int TM, int WP, int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void decode_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    Work w;
+    if (!decode_prologue(a, w)) return;
+    decode_body<TM, WP>(a, w, lds);
+}
+
+template <int TMW, int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void decode_any_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    Work w;
+    if (!decode_prologue(a, w)) return;
+    switch (w.cls) {
+        case 1: decode_body<16, 16>(a, w, lds); break;
+        case 2: decode_body<TMW, 32>(a, w, lds); break;
+        case 3: decode_body<16, 48>(a, w, lds); break;
+        default: decode_body<TMW, 64>(a, w, lds); break;
     }
 }
 

@@ -251,42 +251,21 @@ template <int NM, int NV, int NDS> __device__ __forceinline__ void xdl_interleav
     XInterleave<NM, NV, NDS, 0>::run();
 }
 
-template <int MT, int NTHREADS>
-__global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a) {
+template <int MT>
+__device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, float *lds_f) {
     typedef XLayout<MT> LY;
     constexpr int KJ = LY::KJ, K16 = LY::K16;
     constexpr int NM_INT = 2 * MT * (KJ + K16) * 2, NM_RAW = 2 * MT * (KJ + K16) * 3;   // MFMAs per half-layer
     constexpr int NV = 32 * MT;                 // ALU ops of a half's epilogue: 8*MT activations x (mul, sin, cvt/2, fma, cvt/2)
     constexpr int ND_INT = (KJ + K16) * MT + MT, ND_RAW = 2 * (KJ + K16) * MT + MT;     // LDS reads per half-layer
-    extern __shared__ __attribute__((aligned(16))) float lds_f[];
     char *lds = (char *)lds_f;
-
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const uint32_t slot = blockIdx.x / a.chunks, chunk = blockIdx.x - slot * a.chunks;
-    const uint32_t tile0 = chunk * a.tiles_per_chunk;
-    const uint32_t ntiles_img = (a.HW + 63) >> 6;
-    if (tile0 >= ntiles_img) return;
-    const uint32_t tile1 = min(tile0 + a.tiles_per_chunk, ntiles_img);
-    const size_t plane0 = (size_t)slot * 3 * a.HW;
-
-    const int64_t id = a.ids[slot];
-    if (id < 0 || (uint64_t)id >= a.n_models) {
-        if (!a.handle_bad) return;
-        const uint32_t p0 = tile0 << 6, p1 = min(tile1 << 6, a.HW);
-        for (int c = 0; c < 3; ++c)
-            for (uint32_t p = p0 + tid; p < p1; p += nthreads) {
-                if (a.out_f32) a.out_f32[plane0 + (size_t)c * a.HW + p] = 0.0f;
-                if (a.out_u8) a.out_u8[plane0 + (size_t)c * a.HW + p] = 0;
-            }
-        if (chunk == 0 && tid == 0) atomicAdd(a.status, 1ull);
-        return;
-    }
-    const IndexEntry e = *(const IndexEntry *)(a.blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
-    const uint32_t cls = e.width == 0 ? 1u : (e.width + 15u) >> 4;
-    if (cls != a.cls) return;
+    const uint32_t slot = w.slot, tile0 = w.tile0, tile1 = w.tile1;
+    const size_t plane0 = w.plane0;
+    const IndexEntry e = w.e;
     const int L = e.n_layers;
 
-    uint32_t *stage = (uint32_t *)(lds_f + a.stage_off);
+    uint32_t *stage = (uint32_t *)(lds_f + a.stage_off[MT]);
     {
         const uint4 *src = (const uint4 *)(a.blob + e.off);
         uint4 *dst = (uint4 *)stage;
@@ -295,7 +274,7 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
     // Tiles are handed out through a counter in LDS (it reuses the first word of the staging area,
     // which is dead once the model is expanded): the SIMD arbiter favours its older wavefront, so
     // with a fixed split the favoured waves would finish early and leave the others running alone.
-    xdl_expand_model<MT>(lds, stage, L, a.pre, tid, nthreads, a.stage_off << 2);
+    xdl_expand_model<MT>(lds, stage, L, a.pre, tid, nthreads, a.stage_off[MT] << 2);
     uint32_t *next_tile = stage;
     if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
     __syncthreads();
@@ -414,6 +393,28 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a
         uint32_t nt_ = 0;
         if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
         tile = __builtin_amdgcn_readfirstlane(nt_);
+    }
+}
+
+template <int MT, int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    Work w;
+    if (!decode_prologue(a, w)) return;
+    xdl_body<MT>(a, w, lds_f);
+}
+
+// every width class in one launch (a.cls == 0)
+template <int NTHREADS>
+__global__ __launch_bounds__(NTHREADS) void decode_xdl_any_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    Work w;
+    if (!decode_prologue(a, w)) return;
+    switch (w.cls) {
+        case 1: xdl_body<1>(a, w, lds_f); break;
+        case 2: xdl_body<2>(a, w, lds_f); break;
+        case 3: xdl_body<3>(a, w, lds_f); break;
+        default: xdl_body<4>(a, w, lds_f); break;
     }
 }
 
