@@ -145,7 +145,7 @@ typedef struct {
  * decode): slot s shows model image_ids[s] sampled on an H x W pixel-centre grid,
  * written to out[s][c][i][j], c = 0,1,2 = R,G,B.  image_ids: device, int64[n],
  * repeats allowed.  out: device, contiguous NCHW, 4-byte aligned for fp32.
- * stream: a hipStream_t (NULL = the default stream).  Asynchronous: enqueues kernels
+ * stream: a hipStream_t (NULL = the default stream).  Asynchronous: enqueues one kernel
  * on `stream` and returns; never synchronises, never reads the host copy of the blob.
  * n == 0 is OK and launches nothing.  Host-detectable errors (NULL, n < 0, H or W <= 0,
  * n*3*H*W overflowing int64 / a plane >= 2^31 pixels, misaligned out or affine, bad out_dtype,
@@ -157,6 +157,7 @@ typedef struct {
  * range; sine networks stay within a few tens of radians).  The default split-precision
  * kernels also need |w * w0/2pi| and the coordinate bounds below 6e4 (fp16 range); a store
  * that breaks this is served by the fp32 MFMA kernels automatically.
+ * A store keeps the launch plan of its last decode: use one store from one host thread at a time.
  * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL, NULL}. */
 int rinr_decode_batch(const rinr_store *models, const int64_t *image_ids, int32_t n,
                       int32_t H, int32_t W, void *out, void *stream);
@@ -177,8 +178,8 @@ int rinr_debug_dequant(const rinr_store *store, int64_t id, int32_t layer, float
                        float *bias_out, void *stream);
 
 /* Grid the last decode on this store used (diagnostics / benchmarks):
- * info[0] = kernel launches, info[1] = total workgroups, info[2] = threads per
- * workgroup of the largest class, info[3] = its dynamic LDS bytes. */
+ * info[0] = kernel launches, info[1] = workgroups, info[2] = threads per workgroup,
+ * info[3] = dynamic LDS bytes per workgroup. */
 int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
 
 /* Process-wide tuning knobs for experiments; defaults are what the benchmarks use.

@@ -330,8 +330,9 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
 
     int launches = 0;
     uint32_t big_lds = 0, total_blocks = 0;
-    if (n_classes > 1) {
+    if (n_classes != 1) {
         // ragged store: one grid over all slots, each workgroup runs the body of its slot's class
+        // (an empty store also comes here: every id is out of range and its slot is zero-filled)
         const void *fn = xdl ? (const void *)decode_xdl_any_kernel<kThreads>
                              : (s->tile_rows_wide == 32 ? (const void *)decode_any_kernel<32, kThreads>
                                                         : (const void *)decode_any_kernel<16, kThreads>);

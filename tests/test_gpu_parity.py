@@ -211,6 +211,15 @@ def test_duplicates_bit_identical_and_n0(torch):
     st.close()
 
 
+def test_empty_store_zero_fills_and_counts(torch):
+    st = rinr.Store(rinr.pack([]))
+    assert st.info() == (0, 0, 0)
+    out = torch.full((3, 3, 5, 7), 9.0, device="cuda")
+    st.decode_batch(ids_dev(torch, [0, 1, -5]), 5, 7, out=out)
+    assert st.status() == 3 and not out.cpu().numpy().any()
+    st.close()
+
+
 def test_decode_on_side_stream_and_preallocated_out(torch):
     w = synth.workload(2, n_images=16)
     st = rinr.Store(rinr.pack(w.models))
