@@ -109,7 +109,11 @@ typedef struct rinr_store rinr_store;
  * touching the device; if NULL the blob is copied back from the device once, here, for
  * the same validation.  The store neither copies nor owns the blob: it must stay
  * allocated and unchanged until rinr_store_close.  Must be called with the blob's
- * device current.  Allocates the handle and an 8-byte device status word. */
+ * device current.  Allocates the handle and an 8-byte device status word.
+ * RINR_E_UNSUPPORTED: some model's expanded weights fit the 160 KB of LDS in neither kernel
+ * form (fp32: 4 bytes per padded weight; split precision: 2 bytes for 2..8-bit layers, 4
+ * otherwise).  A store that fits only the split-precision form opens, and decodes that ask
+ * for RINR_FLAG_FP32_MFMA return RINR_E_UNSUPPORTED. */
 int rinr_store_open(const void *device_blob, const void *host_blob, size_t bytes, rinr_store **store);
 int rinr_store_close(rinr_store *store);
 int rinr_store_info(const rinr_store *store, int64_t *n_models, int32_t *max_width, int32_t *max_layers);

@@ -112,7 +112,8 @@ struct rinr_store {
     std::vector<IndexEntry> index;            // host copy of the index (debug export, diagnostics)
     double class_tile_us[kMaxClass + 1];      // modelled time of one 64-pixel tile on one SIMD
     double class_tile_us_xdl[kMaxClass + 1];
-    bool xdl_ok;                              // every weight fits fp16 range after pre-scaling
+    bool xdl_ok;                              // every weight fits fp16 range after pre-scaling, and the models fit LDS
+    bool fp32_ok;                             // the fp32 kernels' expanded models fit LDS
     uint32_t xdl_stage_off[kMaxClass + 1];    // floats
     uint32_t xdl_lds_bytes[kMaxClass + 1];
     // launch plan of the last (n, H*W, threads, knob) combination, reused while they repeat
@@ -211,6 +212,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
             s->class_tile_us_xdl[c] = (mean * 20.0 + 600.0) / 2400.0;
         }
     }
+    s->fp32_ok = true;
     for (uint32_t c = 1; c <= kMaxClass; ++c) {
         s->stage_off[c] = s->lds_bytes[c] = 0;
         if (!sum.class_count[c]) continue;
@@ -218,7 +220,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         const ClassImpl im = impl_for(c, s->tile_rows_wide);
         const uint32_t tot = ((uint32_t)im.total((int)sum.class_max_layers[c]) + 3u) & ~3u;
         const uint64_t need = (uint64_t)tot * 4 + sum.class_max_bytes[c];
-        if (need > kLdsLimit) { delete s; return RINR_E_UNSUPPORTED; }
+        if (need > kLdsLimit) s->fp32_ok = false;      // fp32 weights are twice the size of the split-precision operands
         s->stage_off[c] = tot;
         s->lds_bytes[c] = (uint32_t)need;
         if (hip_fail(hipFuncSetAttribute((const void *)im.decode, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
@@ -228,6 +230,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
             return RINR_E_HIP;
         }
     }
+    if (!s->fp32_ok && !s->xdl_ok) { delete s; return RINR_E_UNSUPPORTED; }     // too deep for LDS in either form
     if (hip_fail(hipFuncSetAttribute((const void *)decode_xdl_any_kernel<kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<16, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<32, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
@@ -316,7 +319,9 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
         a.ns[c] = a.normalize ? opts->norm_scale[c] : 1.0f;
         a.nb[c] = a.normalize ? opts->norm_shift[c] : 0.0f;
     }
-    const bool xdl = s->xdl_ok && !(opts->flags & RINR_FLAG_FP32_MFMA) && !g_force_fp32;
+    const bool want_fp32 = (opts->flags & RINR_FLAG_FP32_MFMA) || g_force_fp32;
+    if (want_fp32 && !s->fp32_ok) return RINR_E_UNSUPPORTED;
+    const bool xdl = s->xdl_ok && !want_fp32;
 
     const uint32_t tiles = (uint32_t)((HW + 63) >> 6);
     const int threads = g_threads ? g_threads : (tiles >= 96 ? 768 : (tiles >= 64 ? 512 : 256));
@@ -421,6 +426,7 @@ extern "C" int rinr_debug_dequant(const rinr_store *s, int64_t id, int32_t layer
     if (layer < 0 || layer >= e.n_layers) return RINR_E_ARG;
     const uint32_t cls = e.width == 0 ? 1u : (e.width + 15u) >> 4;
     if (cls > kMaxClass || !s->sum.class_count[cls]) return RINR_E_FORMAT;
+    if (!s->fp32_ok) return RINR_E_UNSUPPORTED;      // the export reads the fp32 kernels' layout
     const ClassImpl im = impl_for(cls, s->tile_rows_wide);
     hipLaunchKernelGGL(im.debug, dim3(1), dim3(256), s->lds_bytes[cls], (hipStream_t)stream, s->blob, id, (int)layer,
                        s->stage_off[cls], device_out, bias_out);

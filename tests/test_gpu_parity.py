@@ -245,10 +245,22 @@ def test_store_open_validates_on_device_copy(torch):
     with pytest.raises(rinr.RinrError) as e:
         rinr.Store(bad, validate_on_device=True)
     assert e.value.code == rinr.E_FORMAT
-    # too deep for LDS at width 64: valid blob, refused at open
-    deep = synth.make_models(3, np.arange(1), 64, 12, [0] + [8] * 11 + [0], 0.5)
+    # width 64 with 12 sine layers: the fp32 kernels' weights do not fit LDS, the split-precision
+    # operands (8-bit layers: 8 KB each) do; the store opens and refuses only the fp32 mode
+    deep = synth.make_models(3, np.arange(2), 64, 12, [0] + [8] * 11 + [0], 0.5)
+    st = rinr.Store(rinr.pack(deep))
+    ids = ids_dev(torch, [1, 0])
+    got = st.decode_batch_ex(ids, 9, 11, rinr.OUT_F32, rinr.FLAG_NO_CLAMP).cpu().numpy()
+    ref = oracle.decode(deep, [1, 0], 9, 11, clamp=False)
+    assert np.abs(got - ref).max() <= TOL
     with pytest.raises(rinr.RinrError) as e:
-        rinr.Store(rinr.pack(deep))
+        st.decode_batch_ex(ids, 9, 11, rinr.OUT_F32, rinr.FLAG_FP32_MFMA)
+    assert e.value.code == rinr.E_UNSUPPORTED
+    st.close()
+    # raw fp32 hidden layers at that depth fit neither form: refused at open
+    deeper = synth.make_models(3, np.arange(1), 64, 12, [0] * 13, 0.5)
+    with pytest.raises(rinr.RinrError) as e:
+        rinr.Store(rinr.pack(deeper))
     assert e.value.code == rinr.E_UNSUPPORTED
 
 
