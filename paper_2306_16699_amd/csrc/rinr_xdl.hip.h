@@ -1,18 +1,21 @@
 // Split-precision decode kernel: the layers' contractions run on the fp16 matrix cores
-// (v_mfma_f32_16x16x32_f16 / 16x16x16_f16, fp32 accumulate) with every fp32 operand carried
-// as an exact-sum pair of halfs, hi = fp16(x), lo = fp16(x - hi), so a product keeps ~22
-// significant bits:  W*h ~= Wh*hh + Wh*hl + Wl*hh   (the dropped Wl*hl is 2^-22 relative).
+// (v_mfma_f32_32x32x16_f16 / 16x16x32_f16 / 16x16x16_f16, fp32 accumulate) with every fp32
+// operand carried as an exact-sum pair of halfs, hi = fp16(x), lo = fp16(x - hi), so a product
+// keeps ~22 significant bits:  W*h ~= Wh*hh + Wh*hl + Wl*hh   (the dropped Wl*hl is 2^-22 relative).
 // A hidden layer stored as 2..8-bit codes (Sec. IV-B) needs no low part at all: its integers
 // q - zp are exact in fp16, so W*h = scale * (Q*hh + Q*hl) and the scale moves into the sine
 // epilogue.  Unlike fp32 MFMA, the fp16 matrix pipe runs concurrently with the vector ALU on
-// this chip, so the sine + split work of one wavefront hides behind the matrix work of
-// another; the method and its results (Sec. III-B decode) are unchanged.
+// this chip, so the sine + split work hides the matrix work; the method and its results
+// (Sec. III-B decode) are unchanged.
 //
 // Same structure as the fp32 kernel: workgroup = (slot, range of 64-pixel tiles), model
-// expanded once into LDS, activations register-resident across layers.  Tile = 16 rows x 16
-// pixels, lane = (n = lane % 16, g = lane / 16); accumulator register v of a lane holds row
-// 4g + v of its tile.  A 32-deep k-step takes from lane group g the 8 activations that group
-// holds of two consecutive row tiles (2j, 2j+1), so again nothing crosses lanes.
+// expanded once into LDS, activations register-resident across layers.  Tile = TM rows x TM
+// pixels (TM = 32 for padded widths 32 and 64, else 16), lane = (n = lane % TM, g = lane / TM).
+// A lane's accumulator registers come in quads of four consecutive rows; quad Q (counted over
+// all row tiles of the layer) holds rows
+//     TM = 16:  16 Q + 4 g + b            TM = 32:  32 (Q / 4) + 8 (Q % 4) + 4 g + b,   b = 0..3.
+// One MFMA k-step takes 8 halfs per lane = quads 2j and 2j+1 of every lane group, i.e. exactly the
+// activations the lanes already hold, so again nothing crosses lanes between layers.
 #pragma once
 #include "rinr_kernels.hip.h"
 
@@ -30,6 +33,11 @@ __host__ __device__ inline bool xdl_int_layer(uint32_t bits, float scale_pre) {
     return bits >= 2 && bits <= 8 && a >= 1e-12f && a <= 1e12f;
 }
 
+// MFMA tile rows the split-precision kernel uses for a width class (padded width = 16 * cls).
+// The 32-row instruction does twice the work per issue slot; at padded width 32 that pays, at 64 the
+// 16-register accumulator tuples cost more in register pressure than the issue slots give back.
+__host__ __device__ constexpr int xdl_tile_rows(int cls) { return cls == 2 ? 32 : 16; }
+
 struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
     uint32_t off_hi;       // byte offset of the fp16 operand block
     uint32_t off_lo;       // byte offset of the low-part block, 0 = none (integer layer)
@@ -37,54 +45,75 @@ struct XLayer {            // one entry per linear layer, built in LDS by the wo
     uint32_t off_bias;     // byte offset of the fp32 bias tile(s)
 };
 
-template <int MT> struct XLayout {
-    static constexpr int WP = 16 * MT;
-    static constexpr int KJ = MT / 2;              // 32-deep k-steps of a hidden layer
-    static constexpr int K16 = MT % 2;             // plus one 16-deep step for an odd last tile
+template <int TM, int WP> struct XLayout {
+    static constexpr int G = 64 / TM;              // lane groups
+    static constexpr int RV = TM * TM / 64;        // accumulator registers per tile
+    static constexpr int MT = WP / TM;             // row tiles per layer
+    static constexpr int NQ = WP / (4 * G);        // quads per lane over the layer's rows
+    static constexpr int KJ = NQ / 2;              // full k-steps (8 halfs per lane) of a hidden layer
+    static constexpr int K16 = NQ % 2;             // plus one half-depth step for an odd last quad (TM = 16 only)
     static constexpr int TABLE = 16 * 16;          // bytes: one XLayer per linear layer, 16 at most
-    static constexpr int HID = 256 * MT * MT * 2;  // bytes of one hidden operand block
+    static constexpr int HID = WP * WP * 2;        // bytes of one hidden operand block
     static constexpr int FIRST = MT * 64 * 16;     // bytes: [mt][lane][8 halfs], hi and lo in one k-step
-    static constexpr int OUT = (KJ * 64 * 16 + K16 * 64 * 8);   // bytes: one 16-row tile
-    // half index of hidden weight (o, i) inside its block
+    static constexpr int OUT = KJ * 64 * 16 + K16 * 64 * 8;   // bytes: one TM-row tile
+    static constexpr int OUTB = TM * 4;            // bytes of the output layer's bias tile
+    static_assert(WP % TM == 0 && (TM == 16 || K16 == 0), "layout");
+
+    // row r of the layer -> (quad, lane group, position in the quad)
+    static __device__ __forceinline__ void locate(int r, int &q, int &g, int &b) {
+        b = r & 3;
+        if (TM == 16) { q = r >> 4; g = (r >> 2) & 3; }
+        else { q = ((r >> 5) << 2) | ((r >> 3) & 3); g = (r >> 2) & 1; }
+    }
+    // half index of hidden weight (o, i) inside its block: [k-step][row tile][lane][8]
     static __device__ __forceinline__ int idx_hidden(int o, int i) {
-        const int mt = o >> 4, m = o & 15, t = i >> 4, g = (i >> 2) & 3, v = i & 3;
-        if (t < 2 * KJ) return (((t >> 1) * MT + mt) * 64 + g * 16 + m) * 8 + (t & 1) * 4 + v;
-        return KJ * MT * 512 + (mt * 64 + g * 16 + m) * 4 + v;
+        const int mt = o / TM, m = o % TM;
+        int q, g, b;
+        locate(i, q, g, b);
+        if (q < 2 * KJ) return (((q >> 1) * MT + mt) * 64 + g * TM + m) * 8 + (q & 1) * 4 + b;
+        return KJ * MT * 512 + (mt * 64 + g * TM + m) * 4 + b;
     }
-    static __device__ __forceinline__ int idx_first(int o, int e) { return ((o >> 4) * 64 + (o & 15)) * 8 + e; }
-    // output channel c sits in row 4c of the single output tile, i.e. lane group c, register 0
+    static __device__ __forceinline__ int idx_first(int o, int e) { return ((o / TM) * 64 + (o % TM)) * 8 + e; }
+    // output channel c sits in row 4c of the single output tile
     static __device__ __forceinline__ int idx_out(int c, int i) {
-        const int t = i >> 4, g = (i >> 2) & 3, v = i & 3, lane = g * 16 + 4 * c;
-        if (t < 2 * KJ) return ((t >> 1) * 64 + lane) * 8 + (t & 1) * 4 + v;
-        return KJ * 512 + lane * 4 + v;
+        int q, g, b;
+        locate(i, q, g, b);
+        const int lane = g * TM + 4 * c;
+        if (q < 2 * KJ) return ((q >> 1) * 64 + lane) * 8 + (q & 1) * 4 + b;
+        return KJ * 512 + lane * 4 + b;
     }
-    static __device__ __forceinline__ int idx_bias(int o) { return ((o >> 4) * 4 + ((o >> 2) & 3)) * 4 + (o & 3); }
+    // bias tiles are accumulator shaped: [row tile][lane group][register]
+    static __device__ __forceinline__ int idx_bias(int o) {
+        int q, g, b;
+        locate(o % TM, q, g, b);
+        return ((o / TM) * G + g) * RV + q * 4 + b;
+    }
 };
 
-// Bytes of LDS the expanded model needs (without the staging copy of the record).
-// n_int = hidden layers in integer form, n_raw = hidden layers split hi/lo.
-__host__ __device__ inline uint32_t xdl_model_bytes(int mt, int n_layers, int n_int, int n_raw) {
-    const uint32_t wp = 16u * mt, hid = 512u * mt * mt;
-    const uint32_t out = (uint32_t)((mt / 2) * 1024 + (mt % 2) * 512);
-    return 16u * 16u + ((uint32_t)(n_layers - 1) * wp + 16u) * 4u + (uint32_t)mt * 1024u +
-           hid * (uint32_t)(n_int + 2 * n_raw) + 2u * out;
+// Bytes of LDS the expanded model of width class `cls` needs (without the staging copy of the
+// record).  n_int = hidden layers in integer form, n_raw = hidden layers split hi/lo.
+__host__ __device__ inline uint32_t xdl_model_bytes(int cls, int n_layers, int n_int, int n_raw) {
+    const uint32_t tm = (uint32_t)xdl_tile_rows(cls), wp = 16u * cls, g = 64u / tm, nq = wp / (4u * g);
+    const uint32_t out = (nq / 2) * 1024u + (nq % 2) * 512u;
+    return 16u * 16u + ((uint32_t)(n_layers - 1) * wp + tm) * 4u + (wp / tm) * 1024u +
+           wp * wp * 2u * (uint32_t)(n_int + 2 * n_raw) + 2u * out;
 }
 
-template <int MT>
+template <int TM, int WP>
 __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec, int L, float pre, int tid, int nthreads,
                                                  uint32_t total_bytes) {
-    typedef XLayout<MT> LY;
+    typedef XLayout<TM, WP> LY;
     XLayer *tab = (XLayer *)lds;
     for (uint32_t q = tid; q < (total_bytes >> 2); q += nthreads) ((uint32_t *)lds)[q] = 0u;
     __syncthreads();
     if (tid == 0) {
         uint32_t bias = LY::TABLE;
-        uint32_t cur = LY::TABLE + ((uint32_t)(L - 1) * LY::WP + 16u) * 4u;
+        uint32_t cur = LY::TABLE + (uint32_t)(L - 1) * WP * 4u + LY::OUTB;
         for (int l = 0; l < L; ++l) {
             const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
             XLayer e;
             e.off_bias = bias;
-            bias += (l < L - 1 ? LY::WP : 16) * 4;
+            bias += l < L - 1 ? WP * 4 : LY::OUTB;
             e.scale = 1.0f;
             e.off_hi = cur;
             e.off_lo = 0;
@@ -109,7 +138,7 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
                              hi[LY::idx_out(o, i)] = h;
                              lo[LY::idx_out(o, i)] = (_Float16)(v - (float)h);
                          },
-                         [=](int o, float v) { bt[o * 4] = v; });
+                         [=](int o, float v) { bt[LY::idx_bias(4 * o)] = v; });
         } else if (l == 0) {
             expand_layer(rec, r, lane,
                          [=](int o, int i, float v, int) {
@@ -138,14 +167,24 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
     __syncthreads();
 }
 
-__device__ __forceinline__ f32x4 mfma32h(h8v a, h8v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
-__device__ __forceinline__ f32x4 mfma16h(h4v a, h4v b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
+// ---- MFMA wrappers per tile shape -------------------------------------------------------------------
+template <int TM> struct XTile;
+template <> struct XTile<16> {
+    typedef f32x4 acc_t;
+    static __device__ __forceinline__ acc_t mfma(h8v a, h8v b, acc_t c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ acc_t mfma_half(h4v a, h4v b, acc_t c) { return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0); }
+};
+template <> struct XTile<32> {
+    typedef f32x16 acc_t;
+    static __device__ __forceinline__ acc_t mfma(h8v a, h8v b, acc_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ acc_t mfma_half(h4v, h4v, acc_t c) { return c; }     // never used: no odd quad at TM = 32
+};
 
-// sine of the four accumulator values of one tile, then the exact hi/lo split of the results.
+// sine of four accumulator values (one quad), then the exact hi/lo split of the results.
 // neg1 is -1.0f passed as data so that h - float(hi) stays a single mixed-precision fma.
-__device__ __forceinline__ void sine_split(const f32x4 d, float scale, float neg1, h4v &hi, h4v &lo) {
-    const f2v p0 = {sin_rev(d[0] * scale), sin_rev(d[1] * scale)};
-    const f2v p1 = {sin_rev(d[2] * scale), sin_rev(d[3] * scale)};
+__device__ __forceinline__ void sine_split(float d0, float d1, float d2, float d3, float scale, float neg1, h4v &hi, h4v &lo) {
+    const f2v p0 = {sin_rev(d0 * scale), sin_rev(d1 * scale)};
+    const f2v p1 = {sin_rev(d2 * scale), sin_rev(d3 * scale)};
     const h2v a0 = __builtin_convertvector(p0, h2v), a1 = __builtin_convertvector(p1, h2v);
     const f2v r0 = {__builtin_fmaf((float)a0[0], neg1, p0[0]), __builtin_fmaf((float)a0[1], neg1, p0[1])};
     const f2v r1 = {__builtin_fmaf((float)a1[0], neg1, p1[0]), __builtin_fmaf((float)a1[1], neg1, p1[1])};
@@ -154,43 +193,53 @@ __device__ __forceinline__ void sine_split(const f32x4 d, float scale, float neg
     lo = (h4v){b0[0], b0[1], b1[0], b1[1]};
 }
 
-// ---- per-wavefront state of one half (two 16-pixel tiles = 32 pixels) of a 64-pixel tile ----------
-template <int MT> struct XHalf {
-    static constexpr int KJ = MT / 2, KJA = KJ ? KJ : 1;
-    h8v Hh[2][KJA], Hl[2][KJA];     // activations as fp16 hi / lo, operand of the 32-deep k-steps
-    h4v Hh4[2], Hl4[2];             // ... of the 16-deep step (odd MT)
-    f32x4 D[2][MT];                 // accumulators
+// ---- per-wavefront state of one half (32 pixels) of a 64-pixel tile ------------------------------------
+template <int TM, int WP> struct XHalf {
+    typedef XLayout<TM, WP> LY;
+    static constexpr int NTH = 32 / TM;            // pixel tiles in a half: two of 16 pixels, or one of 32
+    static constexpr int KJA = LY::KJ ? LY::KJ : 1;
+    h8v Hh[NTH][KJA], Hl[NTH][KJA];                // activations as fp16 hi / lo, one entry per full k-step
+    h4v Hh4[NTH], Hl4[NTH];                        // ... of the half-depth step (odd last quad)
+    typename XTile<TM>::acc_t D[NTH][LY::MT];      // accumulators
 };
 
-// sine + split of all accumulators of a half: 32*MT VALU instructions (x4 with the scale multiply)
-template <int MT>
-__device__ __forceinline__ void xdl_epilogue(XHalf<MT> &H, float scale, float neg1) {
-    constexpr int KJ = MT / 2;
+// sine + split of all accumulators of a half: WP/2 activations per lane, 4 VALU instructions each
+template <int TM, int WP>
+__device__ __forceinline__ void xdl_epilogue(XHalf<TM, WP> &H, float scale, float neg1) {
+    typedef XLayout<TM, WP> LY;
+    constexpr int QT = LY::RV / 4;                 // quads per tile
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < XHalf<TM, WP>::NTH; ++nt)
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            h4v hi, lo;
-            sine_split(H.D[nt][t], scale, neg1, hi, lo);
-            if (t < 2 * KJ) {
+        for (int t = 0; t < LY::MT; ++t)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    H.Hh[nt][t >> 1][(t & 1) * 4 + v] = hi[v];
-                    H.Hl[nt][t >> 1][(t & 1) * 4 + v] = lo[v];
-                }
-            } else { H.Hh4[nt] = hi; H.Hl4[nt] = lo; }
-        }
+            for (int qq = 0; qq < QT; ++qq) {
+                const int q = t * QT + qq;         // quad index over the layer's rows
+                h4v hi, lo;
+                sine_split(H.D[nt][t][qq * 4 + 0], H.D[nt][t][qq * 4 + 1], H.D[nt][t][qq * 4 + 2], H.D[nt][t][qq * 4 + 3], scale, neg1,
+                           hi, lo);
+                if (q < 2 * LY::KJ) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        H.Hh[nt][q >> 1][(q & 1) * 4 + v] = hi[v];
+                        H.Hl[nt][q >> 1][(q & 1) * 4 + v] = lo[v];
+                    }
+                } else { H.Hh4[nt] = hi; H.Hl4[nt] = lo; }
+            }
 }
 
 // MFMAs of one hidden layer for a half.  LO: the layer has a low weight part (three terms).
-template <int MT, bool LO>
-__device__ __forceinline__ void xdl_hidden(XHalf<MT> &H, const char *lds, const XLayer el, int lane, int g) {
-    constexpr int KJ = MT / 2, K16 = MT % 2;
+template <int TM, int WP, bool LO>
+__device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, const XLayer el, int lane, int g) {
+    typedef XLayout<TM, WP> LY;
+    typedef XTile<TM> T;
+    typedef typename T::acc_t acc_t;
+    constexpr int KJ = LY::KJ, K16 = LY::K16, MT = LY::MT, NTH = XHalf<TM, WP>::NTH;
     const h8v *ah = (const h8v *)(lds + el.off_hi) + lane;
     const h8v *al = (const h8v *)(lds + el.off_lo) + lane;
     const h4v *ah4 = (const h4v *)(lds + el.off_hi + KJ * MT * 1024) + lane;
     const h4v *al4 = (const h4v *)(lds + el.off_lo + KJ * MT * 1024) + lane;
-    const f32x4 *bt = (const f32x4 *)(lds + el.off_bias) + g;
+    const acc_t *bt = (const acc_t *)(lds + el.off_bias) + g;
 #pragma unroll
     for (int j = 0; j < KJ; ++j)
 #pragma unroll
@@ -198,15 +247,15 @@ __device__ __forceinline__ void xdl_hidden(XHalf<MT> &H, const char *lds, const 
             const h8v av = ah[(j * MT + mt) * 64];
             h8v aw;
             if (LO) aw = al[(j * MT + mt) * 64];
-            f32x4 c;
-            if (j == 0) c = bt[mt * 4];
+            acc_t c;
+            if (j == 0) c = bt[mt * LY::G];
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma32h(av, H.Hh[nt][j], j == 0 ? c : H.D[nt][mt]);
+            for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(av, H.Hh[nt][j], j == 0 ? c : H.D[nt][mt]);
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma32h(av, H.Hl[nt][j], H.D[nt][mt]);
+            for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(av, H.Hl[nt][j], H.D[nt][mt]);
             if (LO) {
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma32h(aw, H.Hh[nt][j], H.D[nt][mt]);
+                for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(aw, H.Hh[nt][j], H.D[nt][mt]);
             }
         }
     if (K16) {
@@ -215,49 +264,27 @@ __device__ __forceinline__ void xdl_hidden(XHalf<MT> &H, const char *lds, const 
             const h4v av = ah4[mt * 64];
             h4v aw;
             if (LO) aw = al4[mt * 64];
-            f32x4 c;
-            if (KJ == 0) c = bt[mt * 4];
+            acc_t c;
+            if (KJ == 0) c = bt[mt * LY::G];
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma16h(av, H.Hh4[nt], KJ == 0 ? c : H.D[nt][mt]);
+            for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(av, H.Hh4[nt], KJ == 0 ? c : H.D[nt][mt]);
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma16h(av, H.Hl4[nt], H.D[nt][mt]);
+            for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(av, H.Hl4[nt], H.D[nt][mt]);
             if (LO) {
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) H.D[nt][mt] = mfma16h(aw, H.Hh4[nt], H.D[nt][mt]);
+                for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(aw, H.Hh4[nt], H.D[nt][mt]);
             }
         }
     }
 }
 
-// Tell the scheduler to issue the block just written as: a first batch of LDS reads, then NM x
-// (1 MFMA, its share of the NV vector-ALU ops), feeding the remaining NDS LDS reads in between,
-// so that the matrix pipe works on one half while the ALU does the other half's sine and split.
-template <int NM, int NV, int NDS, int I> struct XInterleave {
-    static __device__ __forceinline__ void run() {
-        constexpr int FIRST = NDS < 6 ? NDS : 6;
-        constexpr int PER = (NV * (I + 1)) / NM - (NV * I) / NM;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if constexpr (PER > 0) __builtin_amdgcn_sched_group_barrier(0x002, PER, 0);
-        if constexpr (FIRST + I < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        XInterleave<NM, NV, NDS, I + 1>::run();
-    }
-};
-template <int NM, int NV, int NDS> struct XInterleave<NM, NV, NDS, NM> {
-    static __device__ __forceinline__ void run() {}
-};
-template <int NM, int NV, int NDS> __device__ __forceinline__ void xdl_interleave() {
-    constexpr int FIRST = NDS < 6 ? NDS : 6;
-    __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);
-    XInterleave<NM, NV, NDS, 0>::run();
-}
-
-template <int MT>
+template <int TM, int WP>
 __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, float *lds_f) {
-    typedef XLayout<MT> LY;
-    constexpr int KJ = LY::KJ, K16 = LY::K16;
-    constexpr int NM_INT = 2 * MT * (KJ + K16) * 2, NM_RAW = 2 * MT * (KJ + K16) * 3;   // MFMAs per half-layer
-    constexpr int NV = 32 * MT;                 // ALU ops of a half's epilogue: 8*MT activations x (mul, sin, cvt/2, fma, cvt/2)
-    constexpr int ND_INT = (KJ + K16) * MT + MT, ND_RAW = 2 * (KJ + K16) * MT + MT;     // LDS reads per half-layer
+    typedef XLayout<TM, WP> LY;
+    typedef XTile<TM> T;
+    typedef typename T::acc_t acc_t;
+    typedef XHalf<TM, WP> Half;
+    constexpr int KJ = LY::KJ, K16 = LY::K16, MT = LY::MT, G = LY::G, NTH = Half::NTH;
     char *lds = (char *)lds_f;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const uint32_t slot = w.slot, tile0 = w.tile0, tile1 = w.tile1;
@@ -265,7 +292,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     const IndexEntry e = w.e;
     const int L = e.n_layers;
 
-    uint32_t *stage = (uint32_t *)(lds_f + a.stage_off[MT]);
+    uint32_t *stage = (uint32_t *)(lds_f + a.stage_off[WP / 16]);
     {
         const uint4 *src = (const uint4 *)(a.blob + e.off);
         uint4 *dst = (uint4 *)stage;
@@ -274,32 +301,30 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     // Tiles are handed out through a counter in LDS (it reuses the first word of the staging area,
     // which is dead once the model is expanded): the SIMD arbiter favours its older wavefront, so
     // with a fixed split the favoured waves would finish early and leave the others running alone.
-    xdl_expand_model<MT>(lds, stage, L, a.pre, tid, nthreads, a.stage_off[MT] << 2);
+    xdl_expand_model<TM, WP>(lds, stage, L, a.pre, tid, nthreads, a.stage_off[WP / 16] << 2);
     uint32_t *next_tile = stage;
     if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
-    const int g = lane >> 4, n = lane & 15;
+    const int g = lane / TM, n = lane % TM;
     const XLayer *tab = (const XLayer *)lds;
     const float neg1 = a.neg1;
     const XLayer e0 = tab[0], eo = tab[L - 1];
     float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
     if (a.affine)
         for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)slot * 6 + q];
-    const float nsc = g == 0 ? a.ns[0] : (g == 1 ? a.ns[1] : a.ns[2]);     // lane group g stores channel g
-    const float nsh = g == 0 ? a.nb[0] : (g == 1 ? a.nb[1] : a.nb[2]);
 
     for (uint32_t tile = tile0 + wave; tile < tile1;) {
-        XHalf<MT> X, Y;
+        Half X, Y;
         // ---- first layer: coordinates as hi/lo halfs in lane group 0; k slots (xh, yh, xl, yl, xh, yh, 0, 0)
         {
             const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
-            const f32x4 *bt = (const f32x4 *)(lds + e0.off_bias) + g;
-            h8v b0[4];
+            const acc_t *bt = (const acc_t *)(lds + e0.off_bias) + g;
+            h8v b0[2 * NTH];
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                uint32_t p = (tile << 6) + nt * 16 + n;
+            for (int nt = 0; nt < 2 * NTH; ++nt) {
+                uint32_t p = (tile << 6) + nt * TM + n;
                 p = min(p, a.HW - 1);
                 const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
                 const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
@@ -313,80 +338,87 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const h8v av = a0[mt * 64];
-                const f32x4 c = bt[mt * 4];
-                X.D[0][mt] = mfma32h(av, b0[0], c);
-                X.D[1][mt] = mfma32h(av, b0[1], c);
-                Y.D[0][mt] = mfma32h(av, b0[2], c);
-                Y.D[1][mt] = mfma32h(av, b0[3], c);
+                const acc_t c = bt[mt * G];
+#pragma unroll
+                for (int nt = 0; nt < NTH; ++nt) {
+                    X.D[nt][mt] = T::mfma(av, b0[nt], c);
+                    Y.D[nt][mt] = T::mfma(av, b0[NTH + nt], c);
+                }
             }
         }
-        xdl_epilogue<MT>(X, 1.0f, neg1);
+        xdl_epilogue<TM, WP>(X, 1.0f, neg1);
         // ---- hidden layers, software-pipelined over the two halves:
         //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
         float scale_prev = 1.0f;
         for (int l = 1; l < L - 1; ++l) {
             const XLayer el = tab[l];
             if (el.off_lo == 0) {
-                xdl_hidden<MT, false>(X, lds, el, lane, g);
-                xdl_epilogue<MT>(Y, scale_prev, neg1);
-                xdl_interleave<NM_INT, NV, ND_INT>();
+                xdl_hidden<TM, WP, false>(X, lds, el, lane, g);
+                xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
                 __builtin_amdgcn_sched_barrier(0);
-                xdl_hidden<MT, false>(Y, lds, el, lane, g);
-                xdl_epilogue<MT>(X, el.scale, neg1);
-                xdl_interleave<NM_INT, NV, ND_INT>();
+                xdl_hidden<TM, WP, false>(Y, lds, el, lane, g);
+                xdl_epilogue<TM, WP>(X, el.scale, neg1);
             } else {
-                xdl_hidden<MT, true>(X, lds, el, lane, g);
-                xdl_epilogue<MT>(Y, scale_prev, neg1);
-                xdl_interleave<NM_RAW, NV, ND_RAW>();
+                xdl_hidden<TM, WP, true>(X, lds, el, lane, g);
+                xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
                 __builtin_amdgcn_sched_barrier(0);
-                xdl_hidden<MT, true>(Y, lds, el, lane, g);
-                xdl_epilogue<MT>(X, el.scale, neg1);
-                xdl_interleave<NM_RAW, NV, ND_RAW>();
+                xdl_hidden<TM, WP, true>(Y, lds, el, lane, g);
+                xdl_epilogue<TM, WP>(X, el.scale, neg1);
             }
             scale_prev = el.scale;
         }
-        xdl_epilogue<MT>(Y, scale_prev, neg1);
-        // ---- output layer width -> 3: one 16-row tile, channel c in row 4c = lane group c, register 0
+        xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
+        // ---- output layer width -> 3: one TM-row tile with channel c in row 4c.  At TM = 16 that is
+        //      register 0 of lane group c; at TM = 32 registers 0 (R) and 4 (B) of group 0, register 0 (G) of group 1.
         {
             const h8v *ah = (const h8v *)(lds + eo.off_hi) + lane;
             const h8v *al = (const h8v *)(lds + eo.off_lo) + lane;
             const h4v *ah4 = (const h4v *)(lds + eo.off_hi + KJ * 1024) + lane;
             const h4v *al4 = (const h4v *)(lds + eo.off_lo + KJ * 1024) + lane;
-            const f32x4 c = ((const f32x4 *)(lds + eo.off_bias))[g];
-            f32x4 O[4] = {c, c, c, c};
+            const acc_t c = ((const acc_t *)(lds + eo.off_bias))[g];
+            acc_t O[2 * NTH];
+#pragma unroll
+            for (int nt = 0; nt < 2 * NTH; ++nt) O[nt] = c;
 #pragma unroll
             for (int j = 0; j < KJ; ++j) {
                 const h8v av = ah[j * 64], aw = al[j * 64];
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    const h8v bh = nt < 2 ? X.Hh[nt][j] : Y.Hh[nt - 2][j];
-                    const h8v bl = nt < 2 ? X.Hl[nt][j] : Y.Hl[nt - 2][j];
-                    O[nt] = mfma32h(av, bh, O[nt]);
-                    O[nt] = mfma32h(av, bl, O[nt]);
-                    O[nt] = mfma32h(aw, bh, O[nt]);
+                for (int nt = 0; nt < 2 * NTH; ++nt) {
+                    const h8v bh = nt < NTH ? X.Hh[nt % NTH][j] : Y.Hh[nt % NTH][j];
+                    const h8v bl = nt < NTH ? X.Hl[nt % NTH][j] : Y.Hl[nt % NTH][j];
+                    O[nt] = T::mfma(av, bh, O[nt]);
+                    O[nt] = T::mfma(av, bl, O[nt]);
+                    O[nt] = T::mfma(aw, bh, O[nt]);
                 }
             }
             if (K16) {
                 const h4v av = ah4[0], aw = al4[0];
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    const h4v bh = nt < 2 ? X.Hh4[nt] : Y.Hh4[nt - 2];
-                    const h4v bl = nt < 2 ? X.Hl4[nt] : Y.Hl4[nt - 2];
-                    O[nt] = mfma16h(av, bh, O[nt]);
-                    O[nt] = mfma16h(av, bl, O[nt]);
-                    O[nt] = mfma16h(aw, bh, O[nt]);
+                for (int nt = 0; nt < 2 * NTH; ++nt) {
+                    const h4v bh = nt < NTH ? X.Hh4[nt % NTH] : Y.Hh4[nt % NTH];
+                    const h4v bl = nt < NTH ? X.Hl4[nt % NTH] : Y.Hl4[nt % NTH];
+                    O[nt] = T::mfma_half(av, bh, O[nt]);
+                    O[nt] = T::mfma_half(av, bl, O[nt]);
+                    O[nt] = T::mfma_half(aw, bh, O[nt]);
                 }
             }
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                float r = O[nt][0];
-                if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
-                if (a.normalize) r = fmaf(r, nsc, nsh);
-                const uint32_t p = (tile << 6) + nt * 16 + n;
-                if (g < 3 && p < a.HW) {
-                    const size_t at = plane0 + (size_t)g * a.HW + p;
-                    if (a.out_f32) a.out_f32[at] = r;
-                    if (a.out_u8) a.out_u8[at] = (uint8_t)rintf(255.0f * r);
+            for (int nt = 0; nt < 2 * NTH; ++nt) {
+                const uint32_t p = (tile << 6) + nt * TM + n;
+                constexpr int NS = TM == 16 ? 1 : 2;     // values a lane may store per pixel tile
+#pragma unroll
+                for (int k = 0; k < NS; ++k) {
+                    const int ch = TM == 16 ? g : (g == 0 ? 2 * k : 1);
+                    const bool live = TM == 16 ? g < 3 : (g == 0 || k == 0);
+                    float r = O[nt][TM == 16 ? 0 : 4 * k];
+                    if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
+                    if (a.normalize)
+                        r = fmaf(r, ch == 0 ? a.ns[0] : (ch == 1 ? a.ns[1] : a.ns[2]), ch == 0 ? a.nb[0] : (ch == 1 ? a.nb[1] : a.nb[2]));
+                    if (live && p < a.HW) {
+                        const size_t at = plane0 + (size_t)ch * a.HW + p;
+                        if (a.out_f32) a.out_f32[at] = r;
+                        if (a.out_u8) a.out_u8[at] = (uint8_t)rintf(255.0f * r);
+                    }
                 }
             }
         }
@@ -396,25 +428,26 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     }
 }
 
-template <int MT, int NTHREADS>
+// One width class per launch (a.cls != 0) ...
+template <int CLS, int NTHREADS>
 __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     Work w;
     if (!decode_prologue(a, w)) return;
-    xdl_body<MT>(a, w, lds_f);
+    xdl_body<xdl_tile_rows(CLS), 16 * CLS>(a, w, lds_f);
 }
 
-// every width class in one launch (a.cls == 0)
+// ... or every width class in one launch (a.cls == 0)
 template <int NTHREADS>
 __global__ __launch_bounds__(NTHREADS) void decode_xdl_any_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     Work w;
     if (!decode_prologue(a, w)) return;
     switch (w.cls) {
-        case 1: xdl_body<1>(a, w, lds_f); break;
-        case 2: xdl_body<2>(a, w, lds_f); break;
-        case 3: xdl_body<3>(a, w, lds_f); break;
-        default: xdl_body<4>(a, w, lds_f); break;
+        case 1: xdl_body<xdl_tile_rows(1), 16>(a, w, lds_f); break;
+        case 2: xdl_body<xdl_tile_rows(2), 32>(a, w, lds_f); break;
+        case 3: xdl_body<xdl_tile_rows(3), 48>(a, w, lds_f); break;
+        default: xdl_body<xdl_tile_rows(4), 64>(a, w, lds_f); break;
     }
 }
 
