@@ -152,7 +152,7 @@ typedef struct {
  * stream: a hipStream_t (NULL = the default stream).  Asynchronous: enqueues one kernel
  * on `stream` and returns; never synchronises, never reads the host copy of the blob.
  * n == 0 is OK and launches nothing.  Host-detectable errors (NULL, n < 0, H or W <= 0,
- * n*3*H*W overflowing int64 / a plane >= 2^31 pixels, misaligned out or affine, bad out_dtype,
+ * n*3*H*W overflowing int64 / the three planes of a slot >= 2^32 pixels, misaligned out or affine, bad out_dtype,
  * NO_CLAMP or NORMALIZE with a uint8 output, non-finite norm values) are returned before
  * anything is enqueued.  An id outside
  * [0, n_models) cannot be seen from the host: that slot is written as zeros and a sticky

@@ -280,7 +280,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
             if (!std::isfinite(opts->norm_scale[c]) || !std::isfinite(opts->norm_shift[c])) return RINR_E_ARG;
     if ((opts->flags & RINR_FLAG_NO_CLAMP) && dt != RINR_OUT_F32) return RINR_E_ARG;
     const int64_t HW = (int64_t)H * W;
-    if (HW >= (int64_t)1 << 31) return RINR_E_SIZE;
+    if (3 * HW >= (int64_t)1 << 32) return RINR_E_SIZE;     // element offsets inside a slot's three planes are 32-bit
     if (n > 0 && HW > INT64_MAX / 3 / n / 4) return RINR_E_SIZE;
     if (n == 0) { std::memset(s->last_info, 0, sizeof s->last_info); return RINR_OK; }
     if (!image_ids || !out) return RINR_E_NULL;

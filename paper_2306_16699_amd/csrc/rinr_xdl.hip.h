@@ -167,6 +167,17 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
     __syncthreads();
 }
 
+// Values every lane holds alike, moved to scalar registers
+__device__ __forceinline__ float uniform_f(float v) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v))); }
+__device__ __forceinline__ XLayer uniform_layer(const XLayer e) {
+    XLayer u;
+    u.off_hi = __builtin_amdgcn_readfirstlane(e.off_hi);
+    u.off_lo = __builtin_amdgcn_readfirstlane(e.off_lo);
+    u.scale = uniform_f(e.scale);
+    u.off_bias = __builtin_amdgcn_readfirstlane(e.off_bias);
+    return u;
+}
+
 // ---- MFMA wrappers per tile shape -------------------------------------------------------------------
 template <int TM> struct XTile;
 template <> struct XTile<16> {
@@ -306,17 +317,28 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
     __syncthreads();
 
-    const int lane = tid & 63, wave = tid >> 6;
-    const int g = lane / TM, n = lane % TM;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const XLayer *tab = (const XLayer *)lds;
     const float neg1 = a.neg1;
-    const XLayer e0 = tab[0], eo = tab[L - 1];
+    const XLayer e0 = uniform_layer(tab[0]), eo = uniform_layer(tab[L - 1]);
+    // per-channel normalisation constants as values (not as an address chosen per lane)
+    const float ns0 = uniform_f(a.ns[0]), ns1 = uniform_f(a.ns[1]), ns2 = uniform_f(a.ns[2]);
+    const float nb0 = uniform_f(a.nb[0]), nb1 = uniform_f(a.nb[1]), nb2 = uniform_f(a.nb[2]);
     float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
     if (a.affine)
-        for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)slot * 6 + q];
+        for (int q = 0; q < 6; ++q) af[q] = uniform_f(a.affine[(size_t)slot * 6 + q]);
 
     for (uint32_t tile = tile0 + wave; tile < tile1;) {
         Half X, Y;
+        // Per-lane values that only the first and the last layer use are derived again for every tile
+        // (the empty asm keeps them from being hoisted): held across the hidden layers they would
+        // push the kernel over its register budget.
+        uint32_t ones = ~0u;
+        asm volatile("" : "+s"(ones));
+        int lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
+        const int g = lane / TM, n = lane % TM;
+        float lo_v = a.lo, af2 = af[2], af5 = af[5];        // second uniform operand of an fma: copied to a vector register at the use
+        asm volatile("" : "+s"(lo_v), "+s"(af2), "+s"(af5));
         // ---- first layer: coordinates as hi/lo halfs in lane group 0; k slots (xh, yh, xl, yl, xh, yh, 0, 0)
         {
             const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
@@ -327,9 +349,9 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
                 uint32_t p = (tile << 6) + nt * TM + n;
                 p = min(p, a.HW - 1);
                 const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
-                const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
-                const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
-                const float x = fmaf(af[0], x0, fmaf(af[1], y0, af[2])), y = fmaf(af[3], x0, fmaf(af[4], y0, af[5]));
+                const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, lo_v);
+                const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, lo_v);
+                const float x = fmaf(af[0], x0, fmaf(af[1], y0, af2)), y = fmaf(af[3], x0, fmaf(af[4], y0, af5));
                 const _Float16 xh = (_Float16)x, yh = (_Float16)y;
                 const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
                 const _Float16 z = (_Float16)0.0f;
@@ -351,23 +373,29 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
         //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
         float scale_prev = 1.0f;
         for (int l = 1; l < L - 1; ++l) {
-            const XLayer el = tab[l];
+            const XLayer el = uniform_layer(tab[l]);
+            int ll = lane;                       // the lane group is derived from the lane index per layer, not kept
+            asm volatile("" : "+v"(ll));
+            const int gl = ll / TM;
             if (el.off_lo == 0) {
-                xdl_hidden<TM, WP, false>(X, lds, el, lane, g);
+                xdl_hidden<TM, WP, false>(X, lds, el, ll, gl);
                 xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
                 __builtin_amdgcn_sched_barrier(0);
-                xdl_hidden<TM, WP, false>(Y, lds, el, lane, g);
+                xdl_hidden<TM, WP, false>(Y, lds, el, ll, gl);
                 xdl_epilogue<TM, WP>(X, el.scale, neg1);
             } else {
-                xdl_hidden<TM, WP, true>(X, lds, el, lane, g);
+                xdl_hidden<TM, WP, true>(X, lds, el, ll, gl);
                 xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
                 __builtin_amdgcn_sched_barrier(0);
-                xdl_hidden<TM, WP, true>(Y, lds, el, lane, g);
+                xdl_hidden<TM, WP, true>(Y, lds, el, ll, gl);
                 xdl_epilogue<TM, WP>(X, el.scale, neg1);
             }
             scale_prev = el.scale;
         }
         xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
+        asm volatile("" : "+s"(ones));           // pixel indices and addresses: derived again rather than kept
+        lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
+        const int go = lane / TM, no = lane % TM;
         // ---- output layer width -> 3: one TM-row tile with channel c in row 4c.  At TM = 16 that is
         //      register 0 of lane group c; at TM = 32 registers 0 (R) and 4 (B) of group 0, register 0 (G) of group 1.
         {
@@ -375,7 +403,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
             const h8v *al = (const h8v *)(lds + eo.off_lo) + lane;
             const h4v *ah4 = (const h4v *)(lds + eo.off_hi + KJ * 1024) + lane;
             const h4v *al4 = (const h4v *)(lds + eo.off_lo + KJ * 1024) + lane;
-            const acc_t c = ((const acc_t *)(lds + eo.off_bias))[g];
+            const acc_t c = ((const acc_t *)(lds + eo.off_bias))[go];
             acc_t O[2 * NTH];
 #pragma unroll
             for (int nt = 0; nt < 2 * NTH; ++nt) O[nt] = c;
@@ -404,20 +432,19 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
             }
 #pragma unroll
             for (int nt = 0; nt < 2 * NTH; ++nt) {
-                const uint32_t p = (tile << 6) + nt * TM + n;
+                const uint32_t p = (tile << 6) + nt * TM + no;
                 constexpr int NS = TM == 16 ? 1 : 2;     // values a lane may store per pixel tile
 #pragma unroll
                 for (int k = 0; k < NS; ++k) {
-                    const int ch = TM == 16 ? g : (g == 0 ? 2 * k : 1);
-                    const bool live = TM == 16 ? g < 3 : (g == 0 || k == 0);
+                    const int ch = TM == 16 ? go : (go == 0 ? 2 * k : 1);
+                    const bool live = TM == 16 ? go < 3 : (go == 0 || k == 0);
                     float r = O[nt][TM == 16 ? 0 : 4 * k];
                     if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
-                    if (a.normalize)
-                        r = fmaf(r, ch == 0 ? a.ns[0] : (ch == 1 ? a.ns[1] : a.ns[2]), ch == 0 ? a.nb[0] : (ch == 1 ? a.nb[1] : a.nb[2]));
+                    if (a.normalize) r = fmaf(r, ch == 0 ? ns0 : (ch == 1 ? ns1 : ns2), ch == 0 ? nb0 : (ch == 1 ? nb1 : nb2));
                     if (live && p < a.HW) {
-                        const size_t at = plane0 + (size_t)ch * a.HW + p;
-                        if (a.out_f32) a.out_f32[at] = r;
-                        if (a.out_u8) a.out_u8[at] = (uint8_t)rintf(255.0f * r);
+                        const uint32_t at = (uint32_t)ch * a.HW + p;  // within the slot's three planes: 3 HW < 2^32 is checked by the host
+                        if (a.out_f32) (a.out_f32 + plane0)[at] = r;
+                        if (a.out_u8) (a.out_u8 + plane0)[at] = (uint8_t)rintf(255.0f * r);
                     }
                 }
             }
