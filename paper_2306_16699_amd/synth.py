@@ -260,3 +260,47 @@ def workload(k: int, n_images: Optional[int] = None, pool: Optional[int] = None,
 def dense_flop_per_pixel(m: Model) -> int:
     """2 * sum(in*out) over the linear layers with their true widths."""
     return 2 * sum(l.n_in * l.n_out for l in m.layers)
+
+
+# ---- inputs of the encode side: target images and initial weights ---------------------------
+
+KIND_IMAGE = 4
+KIND_INIT = 5
+
+
+def images(seed: int, n: int, H: int, W: int) -> np.ndarray:
+    """n procedural RGB images [n, 3, H, W] float32 in [0, 1]: a few smooth waves, a ramp and a soft-edged
+    disc per channel (object boundaries are what INRs find hard).  Stand-ins for the paper's photographs:
+    same shapes and value range, no dataset item reproduced."""
+    ys = (np.arange(H, dtype=np.float64) + 0.5) / H
+    xs = (np.arange(W, dtype=np.float64) + 0.5) / W
+    Y, X = np.meshgrid(ys, xs, indexing="ij")
+    out = np.empty((n, 3, H, W), dtype=np.float32)
+    u = _unit24(stream_bits(stream_key(seed, np.arange(n), 0, KIND_IMAGE), 3 * 16)).reshape(n, 3, 16)
+    for i in range(n):
+        for c in range(3):
+            r = u[i, c]
+            img = 0.5 + 0.25 * (r[0] - 0.5) + 0.3 * (r[1] - 0.5) * (X - 0.5) + 0.3 * (r[2] - 0.5) * (Y - 0.5)
+            for k in range(3):
+                fx, fy, ph, am = 1 + 5 * r[3 + 4 * k], 1 + 5 * r[4 + 4 * k], 2 * math.pi * r[5 + 4 * k], 0.08 + 0.1 * r[6 + 4 * k]
+                img = img + am * np.sin(2 * math.pi * (fx * X + fy * Y) + ph)
+            cx, cy, rad = 0.2 + 0.6 * r[15], 0.2 + 0.6 * r[14], 0.1 + 0.2 * r[13]
+            d = np.sqrt((X - cx) ** 2 + (Y - cy) ** 2)
+            img = img + 0.25 * (r[12] - 0.5) * 2 / (1 + np.exp((d - rad) * 40.0))
+            out[i, c] = np.clip(img, 0.0, 1.0)
+    return out
+
+
+def init_params(seed: int, widths: Sequence[int], n: int, w0: float = 30.0) -> np.ndarray:
+    """Initial parameter vectors [n, n_params] float32 in the layout of the fit API (per layer W then b):
+    first layer U(-1/d_in, 1/d_in), other weights U(+-sqrt(6/d_in)/w0), biases U(+-1/sqrt(d_in))/w0."""
+    parts = []
+    for l in range(len(widths) - 1):
+        nin, nout = widths[l], widths[l + 1]
+        bw = 1.0 / nin if l == 0 else math.sqrt(6.0 / nin) / w0
+        bb = 1.0 / math.sqrt(nin) / w0
+        uw = _unit24(stream_bits(stream_key(seed, np.arange(n), l, KIND_INIT), nout * nin))
+        ub = _unit24(stream_bits(stream_key(seed, np.arange(n), l + 64, KIND_INIT), nout))
+        parts.append((2 * uw - 1) * bw)
+        parts.append((2 * ub - 1) * bb)
+    return np.concatenate(parts, axis=1).astype(np.float32)

@@ -215,3 +215,37 @@ def test_fit_reduces_loss_and_fits_a_constant():
     const = np.broadcast_to(np.array([0.2, 0.5, 0.9])[:, None, None], (3, 4, 4)).copy()
     p, losses = fo.fit([2, 4, 3], np.zeros(fo.n_params([2, 4, 3])), const, steps=400, lr0=2e-2)
     assert losses[-1] < 1e-6 and np.allclose(p[-3:], [0.2, 0.5, 0.9], atol=2e-3)
+
+
+def _grad_matrix_form(widths, p, tgt, w0=30.0, lo=-1.0, hi=1.0):
+    """The same loss gradient written with whole-image matrix products (second, independent statement)."""
+    _, H, W = tgt.shape
+    ys = lo + (hi - lo) * (2 * np.arange(H) + 1) / (2 * H)
+    xs = lo + (hi - lo) * (2 * np.arange(W) + 1) / (2 * W)
+    Y, X = np.meshgrid(ys, xs, indexing="ij")
+    hs, zs, layers, off = [np.stack([X.ravel(), Y.ravel()])], [], [], 0
+    for l in range(len(widths) - 1):
+        nin, nout = widths[l], widths[l + 1]
+        layers.append((p[off:off + nout * nin].reshape(nout, nin), p[off + nout * nin:off + nout * nin + nout]))
+        off += nout * nin + nout
+    for l, (w, b) in enumerate(layers):
+        zs.append(w @ hs[-1] + b[:, None])
+        if l < len(layers) - 1:
+            hs.append(np.sin(w0 * zs[-1]))
+    d = 2.0 / tgt.size * (zs[-1] - tgt.reshape(3, -1))
+    gs = []
+    for l in range(len(layers) - 1, -1, -1):
+        gs.append((d @ hs[l].T, d.sum(axis=1)))
+        if l > 0:
+            d = (layers[l][0].T @ d) * w0 * np.cos(w0 * zs[l - 1])
+    return np.concatenate([np.concatenate([gw.ravel(), gb]) for gw, gb in gs[::-1]])
+
+
+def test_gradient_matches_matrix_form_on_deep_models():
+    rng = np.random.default_rng(12)
+    for widths, H, W in (([2] + [32] * 9 + [3], 12, 10), ([2, 24, 48, 32, 3], 7, 9)):
+        p = rand_params(widths, rng)
+        tgt = rng.uniform(0, 1, (3, H, W))
+        _, g = fo.loss_grad(widths, p, tgt)
+        want = _grad_matrix_form(widths, p, tgt)
+        assert np.abs(g - want).max() <= 1e-11 * np.abs(want).max()

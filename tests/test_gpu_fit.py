@@ -1,0 +1,164 @@
+"""GPU parity of the fitting kernels (include/rinr_fit.h) against the fp64 encode oracle."""
+import numpy as np
+import pytest
+
+from oracle import fit_oracle as fo
+from oracle import oracle as dec
+from paper_2306_16699_amd import rinr, rinr_fit, synth
+
+pytestmark = pytest.mark.gpu
+
+ARCHS = {
+    "cifar 3x15 @32x32": ([2, 15, 15, 15, 3], 32, 32),
+    "flowers 10x32 ragged": ([2] + [32] * 9 + [3], 24, 20),
+    "mini-imagenet 10x40 ragged": ([2] + [40] * 9 + [3], 17, 13),
+    "width 64 x6": ([2] + [64] * 6 + [3], 16, 16),
+    "tapered": ([2, 24, 48, 32, 3], 9, 31),
+    "one hidden unit": ([2, 1, 3], 5, 7),
+    "one pixel": ([2, 8, 3], 1, 1),
+}
+
+
+def targets_of(seed, n, H, W):
+    import torch
+    t = synth.images(seed, n, H, W)
+    return t, torch.from_numpy(t).cuda()
+
+
+def keep_flags(rng, widths, n, prob):
+    ks = []
+    for _ in range(n):
+        mats = [(rng.uniform(size=(widths[l + 1], widths[l])) < prob).astype(np.uint8) for l in range(len(widths) - 1)]
+        ks.append(rinr_fit.weight_keep_flags(widths, mats))
+    return np.stack(ks)
+
+
+@pytest.mark.parametrize("name", list(ARCHS))
+@pytest.mark.parametrize("masked", [False, True])
+def test_loss_and_gradient(name, masked):
+    widths, H, W = ARCHS[name]
+    n = 3
+    rng = np.random.default_rng(len(name))
+    p0 = synth.init_params(7, widths, n)          # the method's own initial scale: larger weights make deep sine nets chaotic in fp32
+    tgt, tgt_d = targets_of(11, n, H, W)
+    keep = keep_flags(rng, widths, n, 0.6) if masked else None
+    lo, hi = (0.0, 1.0) if "tapered" in name else (-1.0, 1.0)
+    f = rinr_fit.Fit(widths, n, H, W, coord_lo=lo, coord_hi=hi)
+    if keep is not None:
+        f.set_keep(keep)
+    f.set_params(p0)
+    loss, grad = f.loss_grad(tgt_d)
+    got_p = f.get_params()
+    for i in range(n):
+        k = None if keep is None else keep[i]
+        pe = p0[i].astype(np.float64) if k is None else p0[i].astype(np.float64) * k
+        assert np.array_equal(got_p[i], pe.astype(np.float32))              # masked parameters were zeroed
+        want_loss, want_g = fo.loss_grad(widths, pe, tgt[i], k, lo=lo, hi=hi)
+        assert abs(loss[i] - want_loss) <= 2e-5 * want_loss + 1e-9, (i, loss[i], want_loss)
+        scale = np.abs(want_g).max()
+        err = np.abs(grad[i] - want_g).max()
+        print(f'{name} masked={masked} image {i}: loss rel err {abs(loss[i] - want_loss) / want_loss:.1e}, grad err / max|grad| {err / scale:.1e}')
+        assert err <= 2e-5 * scale + 1e-9, (i, err, scale)
+        if k is not None:
+            assert not grad[i][k == 0].any()
+    # the printed sum of Eq. 1 (loss_scale = 1) differs from the mean by the factor 3 H W only
+    loss1, grad1 = f.loss_grad(tgt_d, loss_scale=1.0)
+    np.testing.assert_allclose(loss1, loss * 3 * H * W, rtol=1e-5)
+    np.testing.assert_allclose(grad1, grad * 3 * H * W, rtol=1e-4, atol=1e-6 * np.abs(grad1).max())
+    f.close()
+
+
+@pytest.mark.parametrize("name", ["cifar 3x15 @32x32", "mini-imagenet 10x40 ragged", "tapered"])
+def test_adam_steps_follow_the_oracle(name):
+    widths, H, W = ARCHS[name]
+    n, steps, lr, T = 2, 4, 5e-4, 10
+    rng = np.random.default_rng(3)
+    p0 = synth.init_params(5, widths, n)
+    tgt, tgt_d = targets_of(13, n, H, W)
+    keep = keep_flags(rng, widths, n, 0.8)
+    f = rinr_fit.Fit(widths, n, H, W)
+    f.set_keep(keep)
+    f.set_params(p0)
+    losses = []
+    for s in range(steps):                  # one step per call, so that every step's loss can be read
+        f.steps(tgt_d, 1, lr, t0=s, T=T)
+        losses.append(f.last_loss())
+    got = f.get_params()
+    for i in range(n):
+        ref, ref_losses = fo.fit(widths, p0[i], tgt[i], steps, lr, T=T, keep=keep[i])
+        np.testing.assert_allclose([l[i] for l in losses], ref_losses, rtol=3e-4)
+        diff = np.abs(got[i] - ref)
+        # Adam normalises the step to about lr whatever the gradient's size, so an entry whose gradient is
+        # lost in fp32 rounding may move the other way: allow that for a few entries, hold the rest tight
+        assert diff.max() <= 2.0 * steps * lr
+        assert np.mean(diff > 0.02 * lr) < 0.01, np.mean(diff > 0.02 * lr)
+        assert not got[i][keep[i] == 0].any()
+    # the same four steps in one call
+    f.set_params(p0)
+    f.steps(tgt_d, steps, lr, t0=0, T=T)
+    np.testing.assert_array_equal(f.get_params(), got)
+    f.close()
+
+
+def test_fit_prune_quantise_pack_decode_round_trip():
+    import torch
+    widths, H, W, n = [2, 24, 24, 24, 3], 24, 24, 8
+    tgt, tgt_d = targets_of(17, n, H, W)
+    f = rinr_fit.Fit(widths, n, H, W)
+    f.set_params(synth.init_params(19, widths, n))
+    l0, _ = f.loss_grad(tgt_d, want_grad=False)
+    f.steps(tgt_d, 600, 2e-3, t0=0, T=600)
+    l1 = f.last_loss()
+    assert np.all(l1 < 0.1 * l0), (l0, l1)
+    psnr = -10.0 * np.log10(l1)                                  # mean squared error on a 0..1 scale
+    assert psnr.min() > 22.0, psnr
+    # dynamic pruning (Sec. IV-A): ratio from each image's PSNR, magnitude masks per weight matrix, re-fit
+    p = f.get_params()
+    keeps, mats_all = [], []
+    for i in range(n):
+        ratio = rinr_fit.prune_ratio(0, float(psnr[i]) + 8.0)      # shifted so that this small test prunes something
+        mats = [rinr_fit.l1_mask(w, ratio).reshape(w.shape) for w, _ in rinr_fit.split_params(widths, p[i])]
+        mats_all.append(mats)
+        keeps.append(rinr_fit.weight_keep_flags(widths, mats))
+    f.set_keep(np.stack(keeps))
+    f.reset_optimizer()
+    f.steps(tgt_d, 300, 1e-3, t0=0, T=300)
+    l2 = f.last_loss()
+    assert np.all(l2 < 0.2 * l0), (l0, l2)                       # pruned and re-fitted: still a fit, if a coarser one
+    p = f.get_params()
+    assert not p[np.stack(keeps) == 0].any()
+    # quantise the hidden layers to 8 bits (Sec. IV-B), pack, decode with the decode kernels
+    models = [rinr_fit.to_model(widths, p[i], mats_all[i], hidden_bits=8) for i in range(n)]
+    st = rinr.Store(rinr.pack(models))
+    ids = torch.arange(n, dtype=torch.int64, device="cuda")
+    out = st.decode_batch(ids, H, W).cpu().numpy()
+    ref = dec.decode(models, np.arange(n), H, W)
+    assert np.abs(out - ref).max() <= 1e-3
+    mse_q = ((out - tgt) ** 2).reshape(n, -1).mean(axis=1)
+    psnr_q = -10.0 * np.log10(mse_q)
+    assert np.all(psnr_q > -10.0 * np.log10(l2) - 3.0), (psnr_q, -10.0 * np.log10(l2))   # 8-bit hidden layers cost little
+    st.close()
+    f.close()
+
+
+def test_fit_argument_errors_and_empty():
+    import torch
+    with pytest.raises(rinr.RinrError) as e:
+        rinr_fit.Fit([3, 8, 3], 1, 4, 4)
+    assert e.value.code == rinr.E_ARG
+    with pytest.raises(rinr.RinrError) as e:
+        rinr_fit.Fit([2, 65, 3], 1, 4, 4)
+    assert e.value.code == rinr.E_ARG
+    with pytest.raises(rinr.RinrError):
+        rinr_fit.Fit([2, 8, 3], 1, 0, 4)
+    f = rinr_fit.Fit([2, 8, 3], 0, 4, 4)
+    f.steps(torch.empty((0, 3, 4, 4), device="cuda"), 3, 1e-3)
+    assert f.get_params().shape == (0, f.n_params)
+    f.close()
+    f = rinr_fit.Fit([2, 8, 3], 1, 4, 4)
+    t = torch.zeros((1, 3, 4, 4), device="cuda")
+    with pytest.raises(rinr.RinrError):
+        f.steps(t, -1, 1e-3)
+    with pytest.raises(rinr.RinrError):
+        f.steps(t, 1, 1e-3, beta1=1.5)
+    f.close()
