@@ -28,7 +28,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxL = RINR_FIT_MAX_LAYERS;
 constexpr int kWaves = 8, kThreads = kWaves * 64;
-constexpr int kSlots = 3;                          // weight-gradient tiles a wavefront owns per layer: ceil(4 * 5 / 8)
 constexpr uint32_t kLdsLimit = 160 * 1024;
 
 thread_local int g_fit_last_hip = 0;
@@ -39,50 +38,28 @@ inline bool hip_fail(hipError_t e) {
 }
 #define FIT_HIP(call) do { if (hip_fail(call)) return RINR_E_HIP; } while (0)
 
-// LDS layout of one workgroup, in floats.  Row stride of the pixel arrays is PC + 1 and of the weight
-// arrays an odd number too, so that the strided operand reads of the three contractions spread over banks.
-struct Layout {
-    int32_t L, PC, PS;
-    int32_t d[kMaxL + 1];
-    int32_t KP[kMaxL];        // d_in + 1 rounded up to the MFMA depth 4
-    int32_t MP[kMaxL];        // d_out rounded up to 16
-    int32_t NT[kMaxL];        // 16-wide tiles over the d_in + 1 columns of the weight gradient
-    int32_t IT[kMaxL];        // 16-row tiles over d_in (backward contraction output)
-    int32_t w_off[kMaxL], w_ld[kMaxL];   // weights  [MP][w_ld]: column d_in is the bias
-    int32_t h_off[kMaxL];     // layer input [KP][PS]: rows < d_in activations, row d_in ones, rest zero
-    int32_t c_off[kMaxL];     // w0 cos(w0 z_{l-1}) [d_in][PS], l >= 1
-    int32_t d_off[2];         // two buffers [max MP][PS] for the back-propagated error
-    int32_t p_off[kMaxL];     // offset of W_l in the parameter vector
-    int32_t total;            // floats
+// Shapes of one width class (hidden widths padded to DP = 16 * CLS) and pixel chunk PC, and the LDS layout
+// in floats.  Padding is with zero weights, which leaves values and gradients of the real entries unchanged
+// (a padded unit outputs sin(0) = 0 and receives no error), so every hidden layer has the same compile-time
+// shape whatever its true width.  Row strides are odd so that strided operand reads spread over the banks.
+//   W0  [DP][5]        first layer: columns x, y, bias, 0
+//   Wh  [DP][LD] each  layers 1..L-2: columns 0..DP-1 weights, DP bias, then zeros
+//   Wl  [16][LD]       last layer (3 real rows)
+//   H0  [4][PS]        x, y, ones, zeros
+//   Hh  [KP][PS] each  input of layers 1..L-1: rows 0..DP-1 activations, DP ones, then zeros
+//   C   [DP][PS] each  w0 cos(w0 z) of layers 0..L-2
+//   D   [DP][PS] x 2   back-propagated error, ping-pong
+template <int CLS, int PC_> struct Shape {
+    static constexpr int PC = PC_, DP = 16 * CLS, MT = CLS, LD = DP + 5, KP = DP + 4, KS = KP / 4, PS = PC + 1, PT = PC / 16;
+    static constexpr int NIT = MT + 1;                              // column tiles of a hidden weight gradient (bias column included)
+    static constexpr int SLOTS = (MT * NIT + kWaves - 1) / kWaves;  // gradient tiles a wavefront owns per layer
+    static __host__ __device__ constexpr int w_off(int l) { return l == 0 ? 0 : DP * 5 + (l - 1) * DP * LD; }
+    static __host__ __device__ constexpr int w_end(int L) { return DP * 5 + (L - 2) * DP * LD + 16 * LD; }
+    static __host__ __device__ constexpr int h_off(int l, int L) { return w_end(L) + (l == 0 ? 0 : 4 * PS + (l - 1) * KP * PS); }
+    static __host__ __device__ constexpr int c_off(int l, int L) { return w_end(L) + 4 * PS + (L - 1) * KP * PS + l * DP * PS; }   // l = 0..L-2
+    static __host__ __device__ constexpr int d_off(int b, int L) { return c_off(L - 1, L) + b * DP * PS; }
+    static __host__ __device__ constexpr int total(int L) { return d_off(2, L); }
 };
-
-inline bool make_layout(const rinr_fit_arch &arch, int PC, Layout &ly) {
-    std::memset(&ly, 0, sizeof ly);
-    ly.L = arch.n_layers;
-    ly.PC = PC;
-    ly.PS = PC + 1;
-    int off = 0, poff = 0, max_mp = 0;
-    for (int l = 0; l <= ly.L; ++l) ly.d[l] = arch.widths[l];
-    for (int l = 0; l < ly.L; ++l) {
-        const int din = ly.d[l], dout = ly.d[l + 1];
-        ly.KP[l] = (din + 1 + 3) / 4 * 4;
-        ly.MP[l] = (dout + 15) / 16 * 16;
-        ly.NT[l] = (din + 1 + 15) / 16;
-        ly.IT[l] = (din + 15) / 16;
-        ly.w_ld[l] = (ly.KP[l] > ly.IT[l] * 16 ? ly.KP[l] : ly.IT[l] * 16) + 1;
-        ly.w_off[l] = off;
-        off += ly.MP[l] * ly.w_ld[l];
-        ly.p_off[l] = poff;
-        poff += dout * din + dout;
-        if (ly.MP[l] > max_mp) max_mp = ly.MP[l];
-        if ((ly.MP[l] / 16) * ly.NT[l] > kSlots * kWaves) return false;
-    }
-    for (int l = 0; l < ly.L; ++l) { ly.h_off[l] = off; off += ly.KP[l] * ly.PS; }
-    for (int l = 1; l < ly.L; ++l) { ly.c_off[l] = off; off += ly.d[l] * ly.PS; }
-    for (int b = 0; b < 2; ++b) { ly.d_off[b] = off; off += max_mp * ly.PS; }
-    ly.total = off;
-    return true;
-}
 
 struct FitArgs {
     float *params, *m, *v;        // [n_images][n_params]
@@ -95,43 +72,70 @@ struct FitArgs {
     float inv2W, inv2H, lo, span, w0, w0rev;
     float loss_scale;
     float lr, c1inv, c2inv, b1, b2, eps;
-    Layout ly;
+    int32_t L;
+    int32_t d[kMaxL + 1];         // true widths
+    int32_t p_off[kMaxL];         // offset of W_l in the parameter vector
 };
 
 __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
-template <int PC>
+// acc += sum over KSTEPS k-steps of A(ks) x B(ks): one float per lane from LDS at ap[ks * AS], bp[ks * BS].
+// Trip count and strides are compile-time, so the loads become immediate-offset reads issued ahead of the MFMAs.
+template <int KSTEPS, int AS, int BS>
+__device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, bool live, f32x4 acc) {
+    float av[KSTEPS], bv[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        av[ks] = ap[ks * AS];
+        bv[ks] = live ? bp[ks * BS] : 0.0f;
+    }
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) acc = mfma4(av[ks], bv[ks], acc);
+    return acc;
+}
+
+// Where entry (o, i) of layer l's weight-gradient tile lives in the parameter vector, or -1 (padding).
+__device__ __forceinline__ int param_index(const FitArgs &a, int l, int o, int i, int bias_col) {
+    const int din = a.d[l], dout = a.d[l + 1];
+    if (o >= dout) return -1;
+    if (i < din) return a.p_off[l] + o * din + i;
+    if (i == bias_col) return a.p_off[l] + dout * din + o;
+    return -1;
+}
+
+template <int CLS, int PC>
 __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
+    typedef Shape<CLS, PC> S;
+    constexpr int DP = S::DP, MT = S::MT, LD = S::LD, KP = S::KP, KS = S::KS, PS = S::PS, PT = S::PT, NIT = S::NIT, SLOTS = S::SLOTS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ float red[kWaves];
-    const Layout &ly = a.ly;
-    constexpr int PS = PC + 1, PT = PC / 16;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, m = lane & 15, kq = lane >> 4;
-    const int L = ly.L;
+    const int L = a.L;
     const size_t img = blockIdx.x;
     float *P = a.params + img * a.n_params;
+    const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
 
-    // ---- set up: zero everything, weights with the bias as column d_in, rows of ones
-    for (int q = tid; q < ly.total; q += kThreads) lds[q] = 0.0f;
+    // ---- set up: zero everything, weights with the bias as an extra column, rows of ones
+    for (int q = tid; q < S::total(L); q += kThreads) lds[q] = 0.0f;
     __syncthreads();
     for (int l = 0; l < L; ++l) {
-        const int din = ly.d[l], dout = ly.d[l + 1], ld = ly.w_ld[l];
-        float *Wt = lds + ly.w_off[l];
-        const float *src = P + ly.p_off[l];
+        const int din = a.d[l], dout = a.d[l + 1], ld = l == 0 ? 5 : LD, bias_col = l == 0 ? 2 : DP;
+        float *Wt = lds + S::w_off(l);
+        const float *src = P + a.p_off[l];
         for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + e % din] = src[e];
-        for (int o = tid; o < dout; o += kThreads) Wt[o * ld + din] = src[dout * din + o];
-        float *Hl = lds + ly.h_off[l];
-        for (int p = tid; p < PC; p += kThreads) Hl[din * PS + p] = 1.0f;
+        for (int o = tid; o < dout; o += kThreads) Wt[o * ld + bias_col] = src[dout * din + o];
+        float *ones = lds + S::h_off(l, L) + (l == 0 ? 2 : DP) * PS;
+        for (int p = tid; p < PC; p += kThreads) ones[p] = 1.0f;
     }
     __syncthreads();
 
-    f32x4 acc[kMaxL][kSlots];
+    f32x4 acc[kMaxL][SLOTS];
 #pragma unroll
     for (int l = 0; l < kMaxL; ++l)
 #pragma unroll
-        for (int s = 0; s < kSlots; ++s) acc[l][s] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+        for (int s = 0; s < SLOTS; ++s) acc[l][s] = zero4;
     float loss_part = 0.0f;
 
     const uint32_t nchunks = (a.HW + PC - 1) / PC;
@@ -141,41 +145,39 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
             uint32_t p = c * PC + tid;
             p = p < a.HW ? p : a.HW - 1;
             const uint32_t row = p / a.W, col = p - row * a.W;
-            float *H0 = lds + ly.h_off[0];
+            float *H0 = lds + S::h_off(0, L);
             H0[tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
             H0[PS + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
         }
         __syncthreads();
-        // ---- forward
+        // ---- forward: Z_l = W_l H_l, one 16x16 tile (rows mt, pixels nt) per task
         for (int l = 0; l < L; ++l) {
-            const int dout = ly.d[l + 1], ld = ly.w_ld[l], ksteps = ly.KP[l] >> 2;
-            const float *Wt = lds + ly.w_off[l], *Hl = lds + ly.h_off[l];
-            const int ntasks = (ly.MP[l] >> 4) * PT;
+            const bool last = l == L - 1;
+            const int ntasks = (last ? 1 : MT) * PT;
             for (int task = wave; task < ntasks; task += kWaves) {
-                const int mt = task / PT, nt = task - mt * PT;
-                const float *ap = Wt + (mt * 16 + m) * ld + kq, *bp = Hl + kq * PS + nt * 16 + m;
-                f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
-                for (int ks = 0; ks < ksteps; ++ks) z = mfma4(ap[ks * 4], bp[ks * 4 * PS], z);
-                const int col = nt * 16 + m;
-                if (l < L - 1) {
-                    float *Hn = lds + ly.h_off[l + 1], *Cn = lds + ly.c_off[l + 1];
+                const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
+                f32x4 z;
+                if (l == 0)
+                    z = contract<1, 4, 4 * PS>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, lds + S::h_off(0, L) + kq * PS + col, true, zero4);
+                else
+                    z = contract<KS, 4, 4 * PS>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, lds + S::h_off(l, L) + kq * PS + col, true, zero4);
+                if (!last) {
+                    float *Hn = lds + S::h_off(l + 1, L), *Cn = lds + S::c_off(l, L);
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int o = mt * 16 + 4 * kq + v;
-                        if (o < dout) {
-                            const float r = z[v] * a.w0rev;
-                            Hn[o * PS + col] = __builtin_amdgcn_sinf(r);
-                            Cn[o * PS + col] = a.w0 * __builtin_amdgcn_cosf(r);
-                        }
+                        const float r = z[v] * a.w0rev;
+                        Hn[o * PS + col] = __builtin_amdgcn_sinf(r);
+                        Cn[o * PS + col] = a.w0 * __builtin_amdgcn_cosf(r);
                     }
                 } else {
-                    float *D0 = lds + ly.d_off[0];
+                    float *D0 = lds + S::d_off(0, L);
                     const uint32_t pix = c * PC + col;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int o = mt * 16 + 4 * kq + v;
+                        const int o = 4 * kq + v;
                         float e = 0.0f;
-                        if (o < dout && pix < a.HW) e = z[v] - a.target[(img * 3 + o) * a.HW + pix];
+                        if (o < 3 && pix < a.HW) e = z[v] - a.target[(img * 3 + o) * a.HW + pix];
                         loss_part = fmaf(e, e, loss_part);
                         D0[o * PS + col] = 2.0f * a.loss_scale * e;
                     }
@@ -183,43 +185,44 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
             }
             __syncthreads();
         }
-        // ---- backward: weight-gradient tiles into this wavefront's accumulators, error to the layer below
+        // ---- backward.  dW_l += D_l H_l^T into this wavefront's accumulators (tile rows ot, columns it);
+        //      D_{l-1} = (W_l^T D_l) * w0 cos(w0 z_{l-1})  (tile rows it, pixels nt)
         int cur = 0;
 #pragma unroll
         for (int l = kMaxL - 1; l >= 0; --l) {
             if (l < L) {
-                const int din = ly.d[l], ld = ly.w_ld[l], KP = ly.KP[l], NT = ly.NT[l];
-                const float *Wt = lds + ly.w_off[l], *Hl = lds + ly.h_off[l], *Dc = lds + ly.d_off[cur];
-                const int ntasks = (ly.MP[l] >> 4) * NT;
+                const bool last = l == L - 1;
+                const float *Dc = lds + S::d_off(cur, L);
+                if (l == 0) {
 #pragma unroll
-                for (int s = 0; s < kSlots; ++s) {
-                    const int task = wave + s * kWaves;
-                    if (task < ntasks) {
-                        const int ot = task / NT, it = task - ot * NT;
-                        const int i = it * 16 + m;
-                        const bool live = i < KP;
-                        const float *ap = Dc + (ot * 16 + m) * PS + kq, *bp = Hl + (live ? i : 0) * PS + kq;
-                        f32x4 g = acc[l][s];
-#pragma unroll
-                        for (int ks = 0; ks < PC / 4; ++ks) g = mfma4(ap[ks * 4], live ? bp[ks * 4] : 0.0f, g);
-                        acc[l][s] = g;
+                    for (int s = 0; s < SLOTS; ++s) {
+                        const int ot = wave + s * kWaves;
+                        if (ot < MT)
+                            acc[0][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, lds + S::h_off(0, L) + (m < 4 ? m : 0) * PS + kq, m < 4,
+                                                             acc[0][s]);
                     }
-                }
-                if (l > 0) {
-                    float *Dn = lds + ly.d_off[cur ^ 1];
-                    const float *Cl = lds + ly.c_off[l];
-                    const int ksteps = ly.MP[l] >> 2;
-                    const int nt2 = ly.IT[l] * PT;
-                    for (int task = wave; task < nt2; task += kWaves) {
-                        const int it = task / PT, nt = task - it * PT;
-                        const float *ap = Wt + kq * ld + it * 16 + m, *bp = Dc + kq * PS + nt * 16 + m;
-                        f32x4 g = {0.0f, 0.0f, 0.0f, 0.0f};
-                        for (int ks = 0; ks < ksteps; ++ks) g = mfma4(ap[ks * 4 * ld], bp[ks * 4 * PS], g);
-                        const int col = nt * 16 + m;
+                } else {
+                    const int ntasks = (last ? 1 : MT) * NIT;
+#pragma unroll
+                    for (int s = 0; s < SLOTS; ++s) {
+                        const int task = wave + s * kWaves;
+                        if (task < ntasks) {
+                            const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
+                            const bool live = i < KP;
+                            acc[l][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, lds + S::h_off(l, L) + (live ? i : 0) * PS + kq, live,
+                                                             acc[l][s]);
+                        }
+                    }
+                    float *Dn = lds + S::d_off(cur ^ 1, L);
+                    const float *Cl = lds + S::c_off(l - 1, L), *Wt = lds + S::w_off(l);
+                    for (int task = wave; task < MT * PT; task += kWaves) {
+                        const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
+                        const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + kq * PS + col;
+                        const f32x4 g = last ? contract<4, 4 * LD, 4 * PS>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, 4 * PS>(ap, bp, true, zero4);
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
                             const int i = it * 16 + 4 * kq + v;
-                            Dn[i * PS + col] = i < din ? g[v] * Cl[i * PS + col] : 0.0f;
+                            Dn[i * PS + col] = g[v] * Cl[i * PS + col];
                         }
                     }
                 }
@@ -246,19 +249,16 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
 #pragma unroll
     for (int l = 0; l < kMaxL; ++l) {
         if (l < L) {
-            const int din = ly.d[l], dout = ly.d[l + 1], NT = ly.NT[l];
-            const int ntasks = (ly.MP[l] >> 4) * NT;
+            const int nit = l == 0 ? 1 : NIT, ntasks = (l == L - 1 ? 1 : MT) * nit, bias_col = l == 0 ? 2 : DP;
 #pragma unroll
-            for (int s = 0; s < kSlots; ++s) {
+            for (int s = 0; s < SLOTS; ++s) {
                 const int task = wave + s * kWaves;
                 if (task < ntasks) {
-                    const int ot = task / NT, it = task - ot * NT;
-                    const int i = it * 16 + m;
+                    const int ot = task / nit, it = task - ot * nit;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int o = ot * 16 + 4 * kq + v;
-                        if (o < dout && i <= din) {
-                            const int at = ly.p_off[l] + (i < din ? o * din + i : dout * din + o);
+                        const int at = param_index(a, l, ot * 16 + 4 * kq + v, it * 16 + m, bias_col);
+                        if (at >= 0) {
                             const bool kept = !K || K[at];
                             const float g = kept ? acc[l][s][v] : 0.0f;
                             if (G) {
@@ -282,27 +282,50 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
 
 typedef void (*fit_fn)(const FitArgs);
 
+template <int CLS> fit_fn kernel_of(int PC) {
+    switch (PC) {
+        case 64: return fit_step_kernel<CLS, 64>;
+        case 32: return fit_step_kernel<CLS, 32>;
+        default: return fit_step_kernel<CLS, 16>;
+    }
+}
+fit_fn kernel_for(int cls, int PC) {
+    switch (cls) {
+        case 1: return kernel_of<1>(PC);
+        case 2: return kernel_of<2>(PC);
+        case 3: return kernel_of<3>(PC);
+        default: return kernel_of<4>(PC);
+    }
+}
+template <int CLS> int lds_floats_of(int PC, int L) {
+    switch (PC) {
+        case 64: return Shape<CLS, 64>::total(L);
+        case 32: return Shape<CLS, 32>::total(L);
+        default: return Shape<CLS, 16>::total(L);
+    }
+}
+int lds_floats(int cls, int PC, int L) {
+    switch (cls) {
+        case 1: return lds_floats_of<1>(PC, L);
+        case 2: return lds_floats_of<2>(PC, L);
+        case 3: return lds_floats_of<3>(PC, L);
+        default: return lds_floats_of<4>(PC, L);
+    }
+}
+
 }  // namespace
 
 struct rinr_fit {
     rinr_fit_arch arch;
     int64_t n_images, n_params;
     int32_t H, W;
-    int PC;
-    Layout ly;
+    int PC, cls, lds_floats;
+    int32_t p_off[kMaxL];
     float *params, *m, *v, *loss, *scratch_grad;
     uint8_t *keep;            // null until set
     bool has_keep;
     int64_t t;                // Adam steps taken
 };
-
-static fit_fn kernel_for(int PC) {
-    switch (PC) {
-        case 64: return fit_step_kernel<64>;
-        case 32: return fit_step_kernel<32>;
-        default: return fit_step_kernel<16>;
-    }
-}
 
 extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, rinr_fit **out) {
     if (!arch || !out) return RINR_E_NULL;
@@ -323,15 +346,20 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
     f->W = W;
     f->PC = 0;
     const int HW = H * W;
+    int wmax = 1;
+    for (int l = 1; l < arch->n_layers; ++l) wmax = arch->widths[l] > wmax ? arch->widths[l] : wmax;
+    f->cls = (wmax + 15) / 16;
     for (int pc : {64, 32, 16}) {
         if (pc > 16 && pc / 2 >= HW) continue;          // no point in a chunk mostly beyond the image
-        Layout ly;
-        if (!make_layout(*arch, pc, ly)) { delete f; return RINR_E_UNSUPPORTED; }
-        if ((size_t)ly.total * 4 + 256 <= kLdsLimit) { f->PC = pc; f->ly = ly; break; }
+        const int need = lds_floats(f->cls, pc, arch->n_layers);
+        if ((size_t)need * 4 + 256 <= kLdsLimit) { f->PC = pc; f->lds_floats = need; break; }
     }
     if (!f->PC) { delete f; return RINR_E_UNSUPPORTED; }
     f->n_params = 0;
-    for (int l = 0; l < arch->n_layers; ++l) f->n_params += (int64_t)arch->widths[l + 1] * (arch->widths[l] + 1);
+    for (int l = 0; l < arch->n_layers; ++l) {
+        f->p_off[l] = (int32_t)f->n_params;
+        f->n_params += (int64_t)arch->widths[l + 1] * (arch->widths[l] + 1);
+    }
     const size_t np = (size_t)(n_images > 0 ? n_images : 1) * (size_t)f->n_params;
     f->params = f->m = f->v = f->loss = f->scratch_grad = nullptr;
     f->keep = nullptr;
@@ -342,7 +370,7 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
         hip_fail(hipMalloc((void **)&f->loss, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
         hip_fail(hipMemset(f->params, 0, np * 4)) || hip_fail(hipMemset(f->m, 0, np * 4)) ||
         hip_fail(hipMemset(f->v, 0, np * 4)) || hip_fail(hipMemset(f->loss, 0, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
-        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->PC), hipFuncAttributeMaxDynamicSharedMemorySize,
+        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->cls, f->PC), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)kLdsLimit - 256))) {
         rinr_fit_destroy(f);
         return RINR_E_HIP;
@@ -449,8 +477,10 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.c1inv = (float)(1.0 / (1.0 - std::pow((double)b1, (double)t)));
     a.c2inv = (float)(1.0 / (1.0 - std::pow((double)b2, (double)t)));
     a.b1 = b1; a.b2 = b2; a.eps = eps;
-    a.ly = f->ly;
-    hipLaunchKernelGGL(kernel_for(f->PC), dim3((uint32_t)f->n_images), dim3(kThreads), (size_t)f->ly.total * 4, stream, a);
+    a.L = f->arch.n_layers;
+    for (int l = 0; l <= a.L; ++l) a.d[l] = f->arch.widths[l];
+    for (int l = 0; l < a.L; ++l) a.p_off[l] = f->p_off[l];
+    hipLaunchKernelGGL(kernel_for(f->cls, f->PC), dim3((uint32_t)f->n_images), dim3(kThreads), (size_t)f->lds_floats * 4, stream, a);
     FIT_HIP(hipGetLastError());
     return RINR_OK;
 }
