@@ -45,6 +45,65 @@ def host_threads() -> int:
     return n
 
 
+# encode-side shapes: the three model shapes of Sec. VI-A at image sizes of their kind, and the headline decode model
+FIT_SHAPES = {
+    "cifar": ("3 sine layers x 15, 32x32 images", [2, 15, 15, 15, 3], 2048, 32, 32),
+    "flowers": ("9 sine layers x 32, 224x224 images", [2] + [32] * 9 + [3], 256, 224, 224),
+    "imagenet": ("9 sine layers x 40, 224x224 images", [2] + [40] * 9 + [3], 256, 224, 224),
+    "w64": ("6 sine layers x 64 (the cfg4 decode model), 224x224 images", [2] + [64] * 6 + [3], 256, 224, 224),
+}
+
+
+def bench_fit(args) -> int:
+    """One step = one full-batch Adam step (every pixel) of every image's MLP; fp32 MFMA is the bound."""
+    import torch
+    from paper_2306_16699_amd import rinr_fit, synth
+    what, widths, n, H, W = FIT_SHAPES[args.fit]
+    base = torch.from_numpy(synth.images(1, 8, H, W)).cuda()
+    tgt = base.repeat((n + 7) // 8, 1, 1, 1)[:n].contiguous()
+    f = rinr_fit.Fit(widths, n, H, W)
+    f.set_params(np.tile(synth.init_params(2, widths, 8), ((n + 7) // 8, 1))[:n])
+    steps = max(1, min(args.steps, 50))
+    tw, done = time.perf_counter(), 0
+    while done < min(args.warmup, 5) or (time.perf_counter() - tw) * 1e3 < args.min_warmup_ms:
+        f.steps(tgt, 1, 5e-4)
+        torch.cuda.synchronize()
+        done += 1
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    f.steps(tgt, steps, 5e-4, t0=0, T=steps)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    flops = 6.0 * sum(widths[l] * widths[l + 1] for l in range(len(widths) - 1)) * H * W * n   # forward + two backward contractions
+    ach = flops / (kern_ms * 1e-3) / 1e12
+    res = {"metric": "fitted pixel-steps/sec on 1 MI355X (per-image MLP fit, Eq. 1): pixels x Adam steps",
+           "value": n * H * W / (wall_ms * 1e-3), "unit": "pixel-steps/s", "image_steps_per_s": n / (wall_ms * 1e-3),
+           "n_gpus": 1, "steps": steps, "warmup": done, "ms_per_step": wall_ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"fit {args.fit}: {what}", "images": n, "H": H, "W": W, "widths": widths},
+           "roofline": {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                        "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": None, "kernel_ms": kern_ms,
+                        "flop_per_launch": flops, "kernel": "fit_step_kernel (fp32 MFMA 16x16x4 from LDS)"}}
+    if not args.no_cpu_baseline:
+        from oracle import fit_oracle
+        p0 = synth.init_params(2, widths, 1)[0].astype(np.float64)
+        sh, sw = min(H, 32), min(W, 32)                     # one image cropped to 32x32: the oracle is a scalar loop
+        tc = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - tc < 10.0:
+            fit_oracle.loss_grad(widths, p0, synth.images(1, 1, H, W)[0][:, :sh, :sw].astype(np.float64))
+            reps += 1
+        dt = time.perf_counter() - tc
+        res["cpu_baseline"] = {"value": reps * sh * sw / dt, "unit": "pixel-steps/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{reps} loss+gradient evaluations of one {sh}x{sw} crop, fp64 C oracle, one thread, {dt:.1f} s"}
+    f.close()
+    print(json.dumps(res))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +121,8 @@ def main() -> int:
     ap.add_argument("--augment", action="store_true",
                     help="time the decode with a per-slot affine map of the sampling grid and per-channel "
                          "normalisation fused in (fp32 output only)")
+    ap.add_argument("--fit", choices=sorted(FIT_SHAPES), default=None,
+                    help="time the encode side instead: full-batch Adam steps of the per-image fit (one JSON line of its own)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="run only a plain device-to-device copy of MIB MiB per step (counter calibration) and exit")
     args = ap.parse_args()
@@ -87,6 +148,8 @@ def main() -> int:
         print(json.dumps({"copy_calibration_bytes_read": nbytes, "bytes_written": nbytes, "steps": args.steps}))
         return 0
     rinr.lib()
+    if args.fit:
+        return bench_fit(args)
     if args.tile:
         rinr.tune(0, args.tile)
     if args.blocks_per_cu:

@@ -215,7 +215,8 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
                     }
                     float *Dn = lds + S::d_off(cur ^ 1, L);
                     const float *Cl = lds + S::c_off(l - 1, L), *Wt = lds + S::w_off(l);
-                    for (int task = wave; task < MT * PT; task += kWaves) {
+                    // handed out from the last wavefront down: the first ones own more gradient tiles
+                    for (int task = kWaves - 1 - wave; task < MT * PT; task += kWaves) {
                         const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
                         const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + kq * PS + col;
                         const f32x4 g = last ? contract<4, 4 * LD, 4 * PS>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, 4 * PS>(ap, bp, true, zero4);
