@@ -38,27 +38,30 @@ inline bool hip_fail(hipError_t e) {
 }
 #define FIT_HIP(call) do { if (hip_fail(call)) return RINR_E_HIP; } while (0)
 
-// Shapes of one width class (hidden widths padded to DP = 16 * CLS) and pixel chunk PC, and the LDS layout
-// in floats.  Padding is with zero weights, which leaves values and gradients of the real entries unchanged
-// (a padded unit outputs sin(0) = 0 and receives no error), so every hidden layer has the same compile-time
-// shape whatever its true width.  Row strides are odd so that strided operand reads spread over the banks.
+// Shapes of one width class (hidden widths padded to DP = 16 * CLS) and the LDS layout in floats.
+// Padding is with zero weights, which leaves values and gradients of the real entries unchanged (a padded unit
+// outputs sin(0) = 0 and receives no error), so every hidden layer has the same compile-time shape whatever
+// its true width.  Pixels are taken 64 at a time.  Row strides are odd so that strided operand reads spread
+// over the banks.
 //   W0  [DP][5]        first layer: columns x, y, bias, 0
 //   Wh  [DP][LD] each  layers 1..L-2: columns 0..DP-1 weights, DP bias, then zeros
 //   Wl  [16][LD]       last layer (3 real rows)
-//   H0  [4][PS]        x, y, ones, zeros
-//   Hh  [KP][PS] each  input of layers 1..L-1: rows 0..DP-1 activations, DP ones, then zeros
-//   C   [DP][PS] each  w0 cos(w0 z) of layers 0..L-2
-//   D   [DP][PS] x 2   back-propagated error, ping-pong
-template <int CLS, int PC_> struct Shape {
-    static constexpr int PC = PC_, DP = 16 * CLS, MT = CLS, LD = DP + 5, KP = DP + 4, KS = KP / 4, PS = PC + 1, PT = PC / 16;
+//   B0, B1, B2 [KP][PS] three pixel buffers.  Forward: the input of layer l is B[l & 1] (rows 0..DP-1
+//       activations, row DP ones, rest zero; layer 0: rows x, y, ones, zero).  Backward: B0 holds the restored
+//       input of the layer at hand, B1 / B2 the back-propagated error, ping-pong.
+// Pre-activations are not stashed in LDS: the wavefront that computed a tile keeps it in registers until the
+// backward pass has used it (sine again for the weight gradient's operand, cosine for the error).
+template <int CLS> struct Shape {
+    static constexpr int PC = 64, PS = PC + 1, PT = PC / 16;
+    static constexpr int DP = 16 * CLS, MT = CLS, LD = DP + 5, KP = DP + 4, KS = KP / 4;
     static constexpr int NIT = MT + 1;                              // column tiles of a hidden weight gradient (bias column included)
-    static constexpr int SLOTS = (MT * NIT + kWaves - 1) / kWaves;  // gradient tiles a wavefront owns per layer
+    static constexpr int ML = CLS == 4 ? 7 : (CLS == 3 ? 10 : kMaxL);   // deepest model: register budget (and LDS at width 64)
+    static constexpr int ZSLOTS = (MT * PT + kWaves - 1) / kWaves;  // forward tiles a wavefront owns per layer
+    static constexpr int GSLOTS = (MT * NIT + kWaves - 1) / kWaves; // gradient tiles a wavefront owns per layer
     static __host__ __device__ constexpr int w_off(int l) { return l == 0 ? 0 : DP * 5 + (l - 1) * DP * LD; }
     static __host__ __device__ constexpr int w_end(int L) { return DP * 5 + (L - 2) * DP * LD + 16 * LD; }
-    static __host__ __device__ constexpr int h_off(int l, int L) { return w_end(L) + (l == 0 ? 0 : 4 * PS + (l - 1) * KP * PS); }
-    static __host__ __device__ constexpr int c_off(int l, int L) { return w_end(L) + 4 * PS + (L - 1) * KP * PS + l * DP * PS; }   // l = 0..L-2
-    static __host__ __device__ constexpr int d_off(int b, int L) { return c_off(L - 1, L) + b * DP * PS; }
-    static __host__ __device__ constexpr int total(int L) { return d_off(2, L); }
+    static __host__ __device__ constexpr int buf(int b, int L) { return w_end(L) + b * KP * PS; }
+    static __host__ __device__ constexpr int total(int L) { return buf(3, L); }
 };
 
 struct FitArgs {
@@ -80,17 +83,24 @@ struct FitArgs {
 __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
 // acc += sum over KSTEPS k-steps of A(ks) x B(ks): one float per lane from LDS at ap[ks * AS], bp[ks * BS].
-// Trip count and strides are compile-time, so the loads become immediate-offset reads issued ahead of the MFMAs.
+// Trip count and strides are compile-time, so the loads become immediate-offset reads issued ahead of the MFMAs
+// (in groups of eight, which bounds the registers held).
 template <int KSTEPS, int AS, int BS>
 __device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, bool live, f32x4 acc) {
-    float av[KSTEPS], bv[KSTEPS];
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-        av[ks] = ap[ks * AS];
-        bv[ks] = live ? bp[ks * BS] : 0.0f;
+    for (int k0 = 0; k0 < KSTEPS; k0 += 8) {
+        constexpr int G = 8;
+        float av[G], bv[G];
+#pragma unroll
+        for (int u = 0; u < G; ++u)
+            if (k0 + u < KSTEPS) {
+                av[u] = ap[(k0 + u) * AS];
+                bv[u] = live ? bp[(k0 + u) * BS] : 0.0f;
+            }
+#pragma unroll
+        for (int u = 0; u < G; ++u)
+            if (k0 + u < KSTEPS) acc = mfma4(av[u], bv[u], acc);
     }
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) acc = mfma4(av[ks], bv[ks], acc);
     return acc;
 }
 
@@ -103,10 +113,11 @@ __device__ __forceinline__ int param_index(const FitArgs &a, int l, int o, int i
     return -1;
 }
 
-template <int CLS, int PC>
+template <int CLS>
 __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
-    typedef Shape<CLS, PC> S;
-    constexpr int DP = S::DP, MT = S::MT, LD = S::LD, KP = S::KP, KS = S::KS, PS = S::PS, PT = S::PT, NIT = S::NIT, SLOTS = S::SLOTS;
+    typedef Shape<CLS> S;
+    constexpr int DP = S::DP, MT = S::MT, LD = S::LD, KP = S::KP, KS = S::KS, PC = S::PC, PS = S::PS, PT = S::PT, NIT = S::NIT;
+    constexpr int ML = S::ML, ZSLOTS = S::ZSLOTS, GSLOTS = S::GSLOTS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ float red[kWaves];
     const int tid = threadIdx.x;
@@ -116,6 +127,7 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
     const size_t img = blockIdx.x;
     float *P = a.params + img * a.n_params;
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    float *const B0 = lds + S::buf(0, L), *const B1 = lds + S::buf(1, L), *const B2 = lds + S::buf(2, L);
 
     // ---- set up: zero everything, weights with the bias as an extra column, rows of ones
     for (int q = tid; q < S::total(L); q += kThreads) lds[q] = 0.0f;
@@ -126,109 +138,133 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
         const float *src = P + a.p_off[l];
         for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + e % din] = src[e];
         for (int o = tid; o < dout; o += kThreads) Wt[o * ld + bias_col] = src[dout * din + o];
-        float *ones = lds + S::h_off(l, L) + (l == 0 ? 2 : DP) * PS;
-        for (int p = tid; p < PC; p += kThreads) ones[p] = 1.0f;
     }
+    for (int p = tid; p < PC; p += kThreads) B0[DP * PS + p] = B1[DP * PS + p] = 1.0f;
     __syncthreads();
 
-    f32x4 acc[kMaxL][SLOTS];
+    f32x4 acc[ML][GSLOTS];          // weight-gradient tiles, whole step
+    f32x4 zst[ML][ZSLOTS];          // pre-activation tiles of the chunk at hand
 #pragma unroll
-    for (int l = 0; l < kMaxL; ++l)
+    for (int l = 0; l < ML; ++l) {
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) acc[l][s] = zero4;
+        for (int s = 0; s < GSLOTS; ++s) acc[l][s] = zero4;
+#pragma unroll
+        for (int s = 0; s < ZSLOTS; ++s) zst[l][s] = zero4;
+    }
     float loss_part = 0.0f;
 
-    const uint32_t nchunks = (a.HW + PC - 1) / PC;
-    for (uint32_t c = 0; c < nchunks; ++c) {
-        // ---- pixel-centre coordinates of the chunk (a ragged last chunk repeats the last pixel; its error is zeroed)
+    // pixel-centre coordinates of the chunk into rows x, y, ones, zero of B0 (a ragged last chunk repeats the
+    // last pixel; its error is zeroed)
+    auto put_coords = [&](uint32_t c) {
         if (tid < PC) {
             uint32_t p = c * PC + tid;
             p = p < a.HW ? p : a.HW - 1;
             const uint32_t row = p / a.W, col = p - row * a.W;
-            float *H0 = lds + S::h_off(0, L);
-            H0[tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
-            H0[PS + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+            B0[tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
+            B0[PS + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+            B0[2 * PS + tid] = 1.0f;
+            B0[3 * PS + tid] = 0.0f;
         }
+    };
+
+    const uint32_t nchunks = (a.HW + PC - 1) / PC;
+    for (uint32_t c = 0; c < nchunks; ++c) {
+        put_coords(c);
         __syncthreads();
-        // ---- forward: Z_l = W_l H_l, one 16x16 tile (rows mt, pixels nt) per task
-        for (int l = 0; l < L; ++l) {
-            const bool last = l == L - 1;
-            const int ntasks = (last ? 1 : MT) * PT;
-            for (int task = wave; task < ntasks; task += kWaves) {
-                const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
-                f32x4 z;
-                if (l == 0)
-                    z = contract<1, 4, 4 * PS>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, lds + S::h_off(0, L) + kq * PS + col, true, zero4);
-                else
-                    z = contract<KS, 4, 4 * PS>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, lds + S::h_off(l, L) + kq * PS + col, true, zero4);
-                if (!last) {
-                    float *Hn = lds + S::h_off(l + 1, L), *Cn = lds + S::c_off(l, L);
+        // ---- forward: Z_l = W_l H_l, one 16x16 tile (rows mt, pixels nt) per task; H_{l+1} = sin(w0 Z_l)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int o = mt * 16 + 4 * kq + v;
-                        const float r = z[v] * a.w0rev;
-                        Hn[o * PS + col] = __builtin_amdgcn_sinf(r);
-                        Cn[o * PS + col] = a.w0 * __builtin_amdgcn_cosf(r);
-                    }
-                } else {
-                    float *D0 = lds + S::d_off(0, L);
-                    const uint32_t pix = c * PC + col;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int o = 4 * kq + v;
-                        float e = 0.0f;
-                        if (o < 3 && pix < a.HW) e = z[v] - a.target[(img * 3 + o) * a.HW + pix];
-                        loss_part = fmaf(e, e, loss_part);
-                        D0[o * PS + col] = 2.0f * a.loss_scale * e;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-        // ---- backward.  dW_l += D_l H_l^T into this wavefront's accumulators (tile rows ot, columns it);
-        //      D_{l-1} = (W_l^T D_l) * w0 cos(w0 z_{l-1})  (tile rows it, pixels nt)
-        int cur = 0;
-#pragma unroll
-        for (int l = kMaxL - 1; l >= 0; --l) {
+        for (int l = 0; l < ML; ++l) {
             if (l < L) {
                 const bool last = l == L - 1;
-                const float *Dc = lds + S::d_off(cur, L);
-                if (l == 0) {
+                const float *in = (l & 1) ? B1 : B0;
+                float *out = (l & 1) ? B0 : B1;
+                const int ntasks = (last ? 1 : MT) * PT;
 #pragma unroll
-                    for (int s = 0; s < SLOTS; ++s) {
-                        const int ot = wave + s * kWaves;
-                        if (ot < MT)
-                            acc[0][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, lds + S::h_off(0, L) + (m < 4 ? m : 0) * PS + kq, m < 4,
-                                                             acc[0][s]);
-                    }
-                } else {
-                    const int ntasks = (last ? 1 : MT) * NIT;
+                for (int s = 0; s < ZSLOTS; ++s) {
+                    const int task = wave + s * kWaves;
+                    if (task < ntasks) {
+                        const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
+                        f32x4 z;
+                        if (l == 0)
+                            z = contract<1, 4, 4 * PS>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, in + kq * PS + col, true, zero4);
+                        else
+                            z = contract<KS, 4, 4 * PS>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + kq * PS + col, true, zero4);
+                        if (!last) {
+                            zst[l][s] = z;
 #pragma unroll
-                    for (int s = 0; s < SLOTS; ++s) {
-                        const int task = wave + s * kWaves;
-                        if (task < ntasks) {
-                            const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
-                            const bool live = i < KP;
-                            acc[l][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, lds + S::h_off(l, L) + (live ? i : 0) * PS + kq, live,
-                                                             acc[l][s]);
-                        }
-                    }
-                    float *Dn = lds + S::d_off(cur ^ 1, L);
-                    const float *Cl = lds + S::c_off(l - 1, L), *Wt = lds + S::w_off(l);
-                    // handed out from the last wavefront down: the first ones own more gradient tiles
-                    for (int task = kWaves - 1 - wave; task < MT * PT; task += kWaves) {
-                        const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
-                        const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + kq * PS + col;
-                        const f32x4 g = last ? contract<4, 4 * LD, 4 * PS>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, 4 * PS>(ap, bp, true, zero4);
+                            for (int v = 0; v < 4; ++v) out[(mt * 16 + 4 * kq + v) * PS + col] = __builtin_amdgcn_sinf(z[v] * a.w0rev);
+                        } else {
+                            const uint32_t pix = c * PC + col;
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int i = it * 16 + 4 * kq + v;
-                            Dn[i * PS + col] = g[v] * Cl[i * PS + col];
+                            for (int v = 0; v < 4; ++v) {
+                                const int o = 4 * kq + v;
+                                float e = 0.0f;
+                                if (o < 3 && pix < a.HW) e = z[v] - a.target[(img * 3 + o) * a.HW + pix];
+                                loss_part = fmaf(e, e, loss_part);
+                                B2[o * PS + col] = 2.0f * a.loss_scale * e;
+                            }
                         }
                     }
                 }
                 __syncthreads();
-                cur ^= 1;
+            }
+        }
+        // ---- backward, layer by layer: restore H_l into B0; then dW_l += D_l H_l^T into this wavefront's
+        //      accumulators (tile rows ot, columns it) and D_{l-1} = (W_l^T D_l) * w0 cos(w0 z_{l-1}) (tile rows it, pixels nt)
+        float *Dc = B2, *Dn = B1;
+#pragma unroll
+        for (int l = ML - 1; l >= 0; --l) {
+            if (l < L) {
+                const bool last = l == L - 1;
+                if (l == 0) {
+                    put_coords(c);
+                } else {
+#pragma unroll
+                    for (int s = 0; s < ZSLOTS; ++s) {
+                        const int task = wave + s * kWaves;
+                        if (task < MT * PT) {
+                            const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) B0[(mt * 16 + 4 * kq + v) * PS + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v] * a.w0rev);
+                        }
+                    }
+                }
+                __syncthreads();
+                if (l == 0) {
+#pragma unroll
+                    for (int s = 0; s < GSLOTS; ++s) {
+                        const int ot = wave + s * kWaves;
+                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, B0 + (m < 4 ? m : 0) * PS + kq, m < 4, acc[0][s]);
+                    }
+                } else {
+                    const int ntasks = (last ? 1 : MT) * NIT;
+#pragma unroll
+                    for (int s = 0; s < GSLOTS; ++s) {
+                        const int task = wave + s * kWaves;
+                        if (task < ntasks) {
+                            const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
+                            const bool live = i < KP;
+                            acc[l][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, B0 + (live ? i : 0) * PS + kq, live, acc[l][s]);
+                        }
+                    }
+                    const float *Wt = lds + S::w_off(l);
+#pragma unroll
+                    for (int s = 0; s < ZSLOTS; ++s) {
+                        const int task = wave + s * kWaves;
+                        if (task < MT * PT) {
+                            const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
+                            const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + kq * PS + col;
+                            const f32x4 g = last ? contract<4, 4 * LD, 4 * PS>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, 4 * PS>(ap, bp, true, zero4);
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                Dn[(it * 16 + 4 * kq + v) * PS + col] = g[v] * a.w0 * __builtin_amdgcn_cosf(zst[l - 1][s][v] * a.w0rev);
+                        }
+                    }
+                }
+                __syncthreads();
+                float *t = Dc;
+                Dc = Dn;
+                Dn = t;
             }
         }
     }
@@ -248,11 +284,11 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
     const uint8_t *K = a.keep ? a.keep + img * a.n_params : nullptr;
     float *G = a.grad_out ? a.grad_out + img * a.n_params : nullptr;
 #pragma unroll
-    for (int l = 0; l < kMaxL; ++l) {
+    for (int l = 0; l < ML; ++l) {
         if (l < L) {
             const int nit = l == 0 ? 1 : NIT, ntasks = (l == L - 1 ? 1 : MT) * nit, bias_col = l == 0 ? 2 : DP;
 #pragma unroll
-            for (int s = 0; s < SLOTS; ++s) {
+            for (int s = 0; s < GSLOTS; ++s) {
                 const int task = wave + s * kWaves;
                 if (task < ntasks) {
                     const int ot = task / nit, it = task - ot * nit;
@@ -283,34 +319,21 @@ __global__ __launch_bounds__(kThreads) void fit_step_kernel(const FitArgs a) {
 
 typedef void (*fit_fn)(const FitArgs);
 
-template <int CLS> fit_fn kernel_of(int PC) {
-    switch (PC) {
-        case 64: return fit_step_kernel<CLS, 64>;
-        case 32: return fit_step_kernel<CLS, 32>;
-        default: return fit_step_kernel<CLS, 16>;
-    }
-}
-fit_fn kernel_for(int cls, int PC) {
+fit_fn kernel_for(int cls) {
     switch (cls) {
-        case 1: return kernel_of<1>(PC);
-        case 2: return kernel_of<2>(PC);
-        case 3: return kernel_of<3>(PC);
-        default: return kernel_of<4>(PC);
+        case 1: return fit_step_kernel<1>;
+        case 2: return fit_step_kernel<2>;
+        case 3: return fit_step_kernel<3>;
+        default: return fit_step_kernel<4>;
     }
 }
-template <int CLS> int lds_floats_of(int PC, int L) {
-    switch (PC) {
-        case 64: return Shape<CLS, 64>::total(L);
-        case 32: return Shape<CLS, 32>::total(L);
-        default: return Shape<CLS, 16>::total(L);
-    }
-}
-int lds_floats(int cls, int PC, int L) {
+// LDS floats of a model of L linear layers in width class cls, or 0 if the class's kernel is not built that deep
+int lds_floats(int cls, int L) {
     switch (cls) {
-        case 1: return lds_floats_of<1>(PC, L);
-        case 2: return lds_floats_of<2>(PC, L);
-        case 3: return lds_floats_of<3>(PC, L);
-        default: return lds_floats_of<4>(PC, L);
+        case 1: return L <= Shape<1>::ML ? Shape<1>::total(L) : 0;
+        case 2: return L <= Shape<2>::ML ? Shape<2>::total(L) : 0;
+        case 3: return L <= Shape<3>::ML ? Shape<3>::total(L) : 0;
+        default: return L <= Shape<4>::ML ? Shape<4>::total(L) : 0;
     }
 }
 
@@ -346,16 +369,12 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
     f->H = H;
     f->W = W;
     f->PC = 0;
-    const int HW = H * W;
     int wmax = 1;
     for (int l = 1; l < arch->n_layers; ++l) wmax = arch->widths[l] > wmax ? arch->widths[l] : wmax;
     f->cls = (wmax + 15) / 16;
-    for (int pc : {64, 32, 16}) {
-        if (pc > 16 && pc / 2 >= HW) continue;          // no point in a chunk mostly beyond the image
-        const int need = lds_floats(f->cls, pc, arch->n_layers);
-        if ((size_t)need * 4 + 256 <= kLdsLimit) { f->PC = pc; f->lds_floats = need; break; }
-    }
-    if (!f->PC) { delete f; return RINR_E_UNSUPPORTED; }
+    f->lds_floats = lds_floats(f->cls, arch->n_layers);
+    if (f->lds_floats == 0 || (size_t)f->lds_floats * 4 + 256 > kLdsLimit) { delete f; return RINR_E_UNSUPPORTED; }
+    f->PC = 64;
     f->n_params = 0;
     for (int l = 0; l < arch->n_layers; ++l) {
         f->p_off[l] = (int32_t)f->n_params;
@@ -371,7 +390,7 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
         hip_fail(hipMalloc((void **)&f->loss, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
         hip_fail(hipMemset(f->params, 0, np * 4)) || hip_fail(hipMemset(f->m, 0, np * 4)) ||
         hip_fail(hipMemset(f->v, 0, np * 4)) || hip_fail(hipMemset(f->loss, 0, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
-        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->cls, f->PC), hipFuncAttributeMaxDynamicSharedMemorySize,
+        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->cls), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)kLdsLimit - 256))) {
         rinr_fit_destroy(f);
         return RINR_E_HIP;
@@ -481,7 +500,7 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.L = f->arch.n_layers;
     for (int l = 0; l <= a.L; ++l) a.d[l] = f->arch.widths[l];
     for (int l = 0; l < a.L; ++l) a.p_off[l] = f->p_off[l];
-    hipLaunchKernelGGL(kernel_for(f->cls, f->PC), dim3((uint32_t)f->n_images), dim3(kThreads), (size_t)f->lds_floats * 4, stream, a);
+    hipLaunchKernelGGL(kernel_for(f->cls), dim3((uint32_t)f->n_images), dim3(kThreads), (size_t)f->lds_floats * 4, stream, a);
     FIT_HIP(hipGetLastError());
     return RINR_OK;
 }
