@@ -103,6 +103,17 @@ int rinr_fit_loss_grad(rinr_fit *fit, const float *targets, float loss_scale, fl
 /* Per-image loss seen by the most recent step (before its update).  Synchronises with `stream`. */
 int rinr_fit_last_loss(const rinr_fit *fit, float *loss, void *stream);
 
+/* ---- reconstruction quality on the GPU --------------------------------------------------- */
+
+/* Peak signal-to-noise ratio per image, the quantity the pruning ratio is chosen from (Sec. IV-A):
+ * psnr[s] = 10 log10(peak^2 * elems / sum_k (a[s][k] - b[s][k])^2) in dB, +inf where the two are equal.
+ * a, b: device float[n_images][elems] (e.g. a decoded batch and the original images, elems = 3 H W),
+ * 4-byte aligned; psnr: device float[n_images]; peak: the value range (1 for 0..1 images).  One kernel on
+ * `stream`, one workgroup per image, no synchronisation, nothing allocated.
+ * RINR_E_NULL / RINR_E_ARG (negative sizes, peak <= 0) / RINR_E_ALIGN / RINR_E_HIP. */
+int rinr_psnr_batch(const float *a, const float *b, int64_t n_images, int64_t elems, float peak, float *psnr,
+                    void *stream);
+
 #ifdef __cplusplus
 }
 #endif

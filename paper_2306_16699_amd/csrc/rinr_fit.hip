@@ -547,3 +547,48 @@ extern "C" int rinr_fit_last_loss(const rinr_fit *f, float *loss, void *stream) 
     if (f->n_images) FIT_HIP(hipMemcpy(loss, f->loss, (size_t)f->n_images * 4, hipMemcpyDeviceToHost));
     return RINR_OK;
 }
+
+// ---- PSNR per image: a streaming reduction, bound by HBM (8 bytes read per element)
+namespace {
+__global__ __launch_bounds__(1024) void psnr_kernel(const float *a, const float *b, int64_t elems, float peak, float *out) {
+    __shared__ double red[16];
+    const float *pa = a + (size_t)blockIdx.x * (size_t)elems, *pb = b + (size_t)blockIdx.x * (size_t)elems;
+    const int tid = threadIdx.x;
+    double acc = 0.0;
+    // groups of 4 floats where both rows are 16-byte aligned, singly otherwise
+    const bool vec = ((((uintptr_t)pa) | ((uintptr_t)pb)) & 15) == 0;
+    const int64_t nv = vec ? elems / 4 : 0;
+    float part = 0.0f;
+    int since = 0;
+    for (int64_t q = tid; q < nv; q += 1024) {
+        const float4 x = ((const float4 *)pa)[q], y = ((const float4 *)pb)[q];
+        const float d0 = x.x - y.x, d1 = x.y - y.y, d2 = x.z - y.z, d3 = x.w - y.w;
+        part += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
+        if (++since == 64) { acc += (double)part; part = 0.0f; since = 0; }     // keep the fp32 partial sums short
+    }
+    for (int64_t k = nv * 4 + tid; k < elems; k += 1024) {
+        const float d = pa[k] - pb[k];
+        part += d * d;
+    }
+    acc += (double)part;
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double s = 0.0;
+        for (int w = 0; w < 16; ++w) s += red[w];
+        out[blockIdx.x] = s > 0.0 ? (float)(10.0 * log10((double)peak * (double)peak * (double)elems / s)) : INFINITY;
+    }
+}
+}  // namespace
+
+extern "C" int rinr_psnr_batch(const float *a, const float *b, int64_t n_images, int64_t elems, float peak, float *psnr,
+                               void *stream) {
+    if (n_images < 0 || elems < 0 || !(peak > 0.0f) || n_images > ((int64_t)1 << 31) - 1) return RINR_E_ARG;
+    if (n_images == 0) return RINR_OK;
+    if (!psnr || (elems > 0 && (!a || !b))) return RINR_E_NULL;
+    if ((((uintptr_t)a) | ((uintptr_t)b) | ((uintptr_t)psnr)) & 3) return RINR_E_ALIGN;
+    hipLaunchKernelGGL(psnr_kernel, dim3((uint32_t)n_images), dim3(1024), 0, (hipStream_t)stream, a, b, elems, peak, psnr);
+    FIT_HIP(hipGetLastError());
+    return RINR_OK;
+}

@@ -16,7 +16,7 @@ from .synth import Layer, Model
 MAX_LAYERS = 12
 EXPORTS = ["rinr_prune_ratio", "rinr_l1_mask", "rinr_quantize_layer", "rinr_fit_create", "rinr_fit_destroy",
            "rinr_fit_n_params", "rinr_fit_set_params", "rinr_fit_set_keep", "rinr_fit_reset_optimizer",
-           "rinr_fit_get_params", "rinr_fit_steps", "rinr_fit_loss_grad", "rinr_fit_last_loss"]
+           "rinr_fit_get_params", "rinr_fit_steps", "rinr_fit_loss_grad", "rinr_fit_last_loss", "rinr_psnr_batch"]
 
 
 class FitArch(C.Structure):
@@ -52,6 +52,7 @@ def lib():
         L.rinr_fit_steps.argtypes = [vp, vp, i32, C.POINTER(FitOpts), vp]
         L.rinr_fit_loss_grad.argtypes = [vp, vp, C.c_float, vp, vp, vp]
         L.rinr_fit_last_loss.argtypes = [vp, vp, vp]
+        L.rinr_psnr_batch.argtypes = [vp, vp, i64, i64, C.c_float, vp, vp]
         _ready = True
     return L
 
@@ -78,6 +79,19 @@ def quantize_layer(w: np.ndarray, bits: int, keep: Optional[np.ndarray] = None):
     rinr._check(lib().rinr_quantize_layer(w.ctypes.data, None if keep is None else keep.ctypes.data, w.size, bits,
                                           C.byref(scale), C.byref(zp), codes.ctypes.data), "rinr_quantize_layer")
     return np.float32(scale.value), int(zp.value), codes
+
+
+def psnr_batch(a, b, peak: float = 1.0, stream=None):
+    """PSNR in dB per image of two device float32 tensors [n, ...] (torch); returns a device tensor [n]."""
+    import torch
+    assert a.is_cuda and b.is_cuda and a.dtype == torch.float32 and b.dtype == torch.float32
+    assert a.shape == b.shape and a.is_contiguous() and b.is_contiguous()
+    n = a.shape[0]
+    out = torch.empty((n,), dtype=torch.float32, device=a.device)
+    elems = a.numel() // n if n else 0
+    rinr._check(lib().rinr_psnr_batch(a.data_ptr(), b.data_ptr(), n, elems, peak, out.data_ptr(), rinr._stream_ptr(stream)),
+                "rinr_psnr_batch")
+    return out
 
 
 class Fit:

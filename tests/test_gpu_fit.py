@@ -162,3 +162,27 @@ def test_fit_argument_errors_and_empty():
     with pytest.raises(rinr.RinrError):
         f.steps(t, 1, 1e-3, beta1=1.5)
     f.close()
+
+
+def test_psnr_batch_matches_the_oracle():
+    import torch
+    rng = np.random.default_rng(21)
+    for n, shape in ((5, (3, 17, 13)), (3, (3, 64, 64)), (2, (1,)), (4, (3, 224, 224))):
+        a = rng.uniform(0, 1, (n,) + shape).astype(np.float32)
+        b = np.clip(a + rng.normal(scale=0.03, size=a.shape), 0, 1).astype(np.float32)
+        b[0] = a[0]                                             # identical pair: +inf
+        got = rinr_fit.psnr_batch(torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda()).cpu().numpy()
+        assert np.isinf(got[0]) and got[0] > 0
+        for i in range(1, n):
+            assert abs(got[i] - fo.psnr(a[i], b[i])) < 2e-4, (shape, i, got[i], fo.psnr(a[i], b[i]))
+        got255 = rinr_fit.psnr_batch(torch.from_numpy(a * 255).cuda(), torch.from_numpy(b * 255).cuda(), peak=255.0).cpu().numpy()
+        np.testing.assert_allclose(got255[1:], got[1:], atol=2e-3)
+    # a view that is 4- but not 16-byte aligned takes the scalar path
+    base = torch.from_numpy(rng.uniform(0, 1, 2 * 101 + 1).astype(np.float32)).cuda()
+    x, y = base[1:].view(2, 101), (base[1:] * 0.5).view(2, 101).contiguous()
+    got = rinr_fit.psnr_batch(x, y).cpu().numpy()
+    xh = base[1:].cpu().numpy().reshape(2, 101)
+    for i in range(2):
+        assert abs(got[i] - fo.psnr(xh[i], xh[i] * 0.5)) < 2e-4
+    with pytest.raises(rinr.RinrError):
+        rinr_fit.psnr_batch(x, y, peak=0.0)
