@@ -54,7 +54,8 @@ template <int TM, int WP> struct XLayout {
     static constexpr int K16 = NQ % 2;             // plus one half-depth step for an odd last quad (TM = 16 only)
     static constexpr int TABLE = 16 * 16;          // bytes: one XLayer per linear layer, 16 at most
     static constexpr int HID = WP * WP * 2;        // bytes of one hidden operand block
-    static constexpr int FIRST = MT * 64 * 16;     // bytes: [mt][lane][8 halfs], hi and lo in one k-step
+    static constexpr int FIRST = G * MT * 64 * 16; // bytes: [pixel tile q][mt][lane][8 halfs], hi and lo in one k-step; variant q has the
+                                                   // weights in lane group q's k-slots only, so that group q's coordinates alone count
     static constexpr int OUT = KJ * 64 * 16 + K16 * 64 * 8;   // bytes: one TM-row tile
     static constexpr int OUTB = TM * 4;            // bytes of the output layer's bias tile
     static_assert(WP % TM == 0 && (TM == 16 || K16 == 0), "layout");
@@ -73,7 +74,7 @@ template <int TM, int WP> struct XLayout {
         if (q < 2 * KJ) return (((q >> 1) * MT + mt) * 64 + g * TM + m) * 8 + (q & 1) * 4 + b;
         return KJ * MT * 512 + (mt * 64 + g * TM + m) * 4 + b;
     }
-    static __device__ __forceinline__ int idx_first(int o, int e) { return ((o / TM) * 64 + (o % TM)) * 8 + e; }
+    static __device__ __forceinline__ int idx_first(int q, int o, int e) { return (((q * MT + o / TM) * 64) + q * TM + (o % TM)) * 8 + e; }
     // output channel c sits in row 4c of the single output tile
     static __device__ __forceinline__ int idx_out(int c, int i) {
         int q, g, b;
@@ -95,7 +96,7 @@ template <int TM, int WP> struct XLayout {
 __host__ __device__ inline uint32_t xdl_model_bytes(int cls, int n_layers, int n_int, int n_raw) {
     const uint32_t tm = (uint32_t)xdl_tile_rows(cls), wp = 16u * cls, g = 64u / tm, nq = wp / (4u * g);
     const uint32_t out = (nq / 2) * 1024u + (nq % 2) * 512u;
-    return 16u * 16u + ((uint32_t)(n_layers - 1) * wp + tm) * 4u + (wp / tm) * 1024u +
+    return 16u * 16u + ((uint32_t)(n_layers - 1) * wp + tm) * 4u + g * (wp / tm) * 1024u +
            wp * wp * 2u * (uint32_t)(n_int + 2 * n_raw) + 2u * out;
 }
 
@@ -144,9 +145,11 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
                          [=](int o, int i, float v, int) {
                              const float w = v * pre;
                              const _Float16 h = (_Float16)w, lw = (_Float16)(w - (float)h);
-                             hi[LY::idx_first(o, i)] = h;          // pairs with the coordinate's high half
-                             hi[LY::idx_first(o, 2 + i)] = h;      // ... with its low half
-                             hi[LY::idx_first(o, 4 + i)] = lw;     // low weight part x high coordinate half
+                             for (int q = 0; q < LY::G; ++q) {
+                                 hi[LY::idx_first(q, o, i)] = h;          // pairs with the coordinate's high half
+                                 hi[LY::idx_first(q, o, 2 + i)] = h;      // ... with its low half
+                                 hi[LY::idx_first(q, o, 4 + i)] = lw;     // low weight part x high coordinate half
+                             }
                          },
                          [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre; });
         } else if (e.off_lo == 0) {
@@ -336,35 +339,32 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
         uint32_t ones = ~0u;
         asm volatile("" : "+s"(ones));
         int lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
-        const int g = lane / TM, n = lane % TM;
+        const int g = lane / TM;
         float lo_v = a.lo, af2 = af[2], af5 = af[5];        // second uniform operand of an fma: copied to a vector register at the use
         asm volatile("" : "+s"(lo_v), "+s"(af2), "+s"(af5));
-        // ---- first layer: coordinates as hi/lo halfs in lane group 0; k slots (xh, yh, xl, yl, xh, yh, 0, 0)
+        // ---- first layer: every lane forms the coordinates of its own pixel (tile * 64 + lane) as hi/lo halfs in
+        //      k slots (xh, yh, xl, yl, xh, yh, 0, 0); the MFMA of pixel tile q uses the weight variant whose
+        //      non-zero k slots are lane group q's, so one operand register set serves all pixel tiles
         {
             const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
             const acc_t *bt = (const acc_t *)(lds + e0.off_bias) + g;
-            h8v b0[2 * NTH];
-#pragma unroll
-            for (int nt = 0; nt < 2 * NTH; ++nt) {
-                uint32_t p = (tile << 6) + nt * TM + n;
-                p = min(p, a.HW - 1);
-                const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
-                const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, lo_v);
-                const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, lo_v);
-                const float x = fmaf(af[0], x0, fmaf(af[1], y0, af2)), y = fmaf(af[3], x0, fmaf(af[4], y0, af5));
-                const _Float16 xh = (_Float16)x, yh = (_Float16)y;
-                const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
-                const _Float16 z = (_Float16)0.0f;
-                b0[nt] = g == 0 ? (h8v){xh, yh, xl, yl, xh, yh, z, z} : (h8v){z, z, z, z, z, z, z, z};
-            }
+            uint32_t p = (tile << 6) + (uint32_t)lane;
+            p = min(p, a.HW - 1);
+            const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
+            const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, lo_v);
+            const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, lo_v);
+            const float x = fmaf(af[0], x0, fmaf(af[1], y0, af2)), y = fmaf(af[3], x0, fmaf(af[4], y0, af5));
+            const _Float16 xh = (_Float16)x, yh = (_Float16)y;
+            const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
+            const _Float16 z = (_Float16)0.0f;
+            const h8v b0 = {xh, yh, xl, yl, xh, yh, z, z};
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const h8v av = a0[mt * 64];
                 const acc_t c = bt[mt * G];
 #pragma unroll
                 for (int nt = 0; nt < NTH; ++nt) {
-                    X.D[nt][mt] = T::mfma(av, b0[nt], c);
-                    Y.D[nt][mt] = T::mfma(av, b0[NTH + nt], c);
+                    X.D[nt][mt] = T::mfma(a0[(nt * MT + mt) * 64], b0, c);
+                    Y.D[nt][mt] = T::mfma(a0[((NTH + nt) * MT + mt) * 64], b0, c);
                 }
             }
         }
