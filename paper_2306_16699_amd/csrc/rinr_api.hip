@@ -37,15 +37,26 @@ typedef void (*debug_fn)(const uint8_t *, int64_t, int, uint32_t, float *, float
 
 struct ClassImpl {
     decode_fn decode;      // fp32 MFMA kernel
-    decode_fn decode_xdl;  // split-precision fp16 MFMA kernel
+    decode_fn decode_xdl[3];  // split-precision fp16 MFMA kernel, per kind of hidden layers (kHiddenAllInt, AllRaw, Mixed)
     debug_fn debug;
     int (*total)(int L);   // expanded floats for L layers (fp32 kernel)
 };
 
 template <int TM, int WP> int total_of(int L) { return Layout<TM, WP>::total(L); }
 template <int TM, int WP> ClassImpl make_impl() {
-    return ClassImpl{decode_kernel<TM, WP, kThreads>, decode_xdl_kernel<WP / 16, kThreads>, dequant_debug_kernel<TM, WP>,
+    return ClassImpl{decode_kernel<TM, WP, kThreads>,
+                     {decode_xdl_kernel<WP / 16, kThreads, kHiddenAllInt>, decode_xdl_kernel<WP / 16, kThreads, kHiddenAllRaw>,
+                      decode_xdl_kernel<WP / 16, kThreads, kHiddenMixed>},
+                     dequant_debug_kernel<TM, WP>,
                      total_of<TM, WP>};
+}
+
+const void *xdl_any_fn(int kind) {
+    switch (kind) {
+        case kHiddenAllInt: return (const void *)decode_xdl_any_kernel<kThreads, kHiddenAllInt>;
+        case kHiddenAllRaw: return (const void *)decode_xdl_any_kernel<kThreads, kHiddenAllRaw>;
+        default: return (const void *)decode_xdl_any_kernel<kThreads, kHiddenMixed>;
+    }
 }
 
 ClassImpl impl_for(uint32_t cls, int tile_rows_wide) {
@@ -113,6 +124,7 @@ struct rinr_store {
     double class_tile_us[kMaxClass + 1];      // modelled time of one 64-pixel tile on one SIMD
     double class_tile_us_xdl[kMaxClass + 1];
     bool xdl_ok;                              // every weight fits fp16 range after pre-scaling, and the models fit LDS
+    int hidden_kind;                          // kHiddenAllInt / AllRaw / Mixed over all hidden layers of all models
     bool fp32_ok;                             // the fp32 kernels' expanded models fit LDS
     uint32_t xdl_stage_off[kMaxClass + 1];    // floats
     uint32_t xdl_lds_bytes[kMaxClass + 1];
@@ -179,6 +191,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         uint32_t need[kMaxClass + 1] = {0, 0, 0, 0, 0};
         double acts[kMaxClass + 1] = {0, 0, 0, 0, 0};
         s->xdl_ok = std::fabs(sum.header.coord_lo) < 60000.0f && std::fabs(sum.header.coord_hi) < 60000.0f;   // coordinates travel as fp16 hi+lo
+        int64_t tot_int = 0, tot_raw = 0;
         for (const IndexEntry &e : s->index) {
             const uint32_t c = e.width == 0 ? 1u : (e.width + 15u) >> 4;
             int n_int = 0, n_raw = 0;
@@ -199,10 +212,13 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
                 }
                 if (!(wmax * std::fabs(k) < 60000.0f)) s->xdl_ok = false;
             }
+            tot_int += n_int;
+            tot_raw += n_raw;
             const uint32_t b = xdl_model_bytes((int)c, e.n_layers, n_int, n_raw);
             if (b > need[c]) need[c] = b;
             acts[c] += (e.n_layers - 1) * 16.0 * c;
         }
+        s->hidden_kind = tot_raw == 0 ? kHiddenAllInt : (tot_int == 0 ? kHiddenAllRaw : kHiddenMixed);
         for (uint32_t c = 1; c <= kMaxClass; ++c) {
             s->xdl_stage_off[c] = need[c] / 4;
             s->xdl_lds_bytes[c] = need[c] + sum.class_max_bytes[c];
@@ -224,14 +240,18 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         s->stage_off[c] = tot;
         s->lds_bytes[c] = (uint32_t)need;
         if (hip_fail(hipFuncSetAttribute((const void *)im.decode, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
-            hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+            hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[0], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+            hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[1], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+            hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[2], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
             hip_fail(hipFuncSetAttribute((const void *)im.debug, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
             delete s;
             return RINR_E_HIP;
         }
     }
     if (!s->fp32_ok && !s->xdl_ok) { delete s; return RINR_E_UNSUPPORTED; }     // too deep for LDS in either form
-    if (hip_fail(hipFuncSetAttribute((const void *)decode_xdl_any_kernel<kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+    if (hip_fail(hipFuncSetAttribute(xdl_any_fn(kHiddenAllInt), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+        hip_fail(hipFuncSetAttribute(xdl_any_fn(kHiddenAllRaw), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+        hip_fail(hipFuncSetAttribute(xdl_any_fn(kHiddenMixed), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<16, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<32, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
         delete s;
@@ -338,7 +358,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (n_classes != 1) {
         // ragged store: one grid over all slots, each workgroup runs the body of its slot's class
         // (an empty store also comes here: every id is out of range and its slot is zero-filled)
-        const void *fn = xdl ? (const void *)decode_xdl_any_kernel<kThreads>
+        const void *fn = xdl ? xdl_any_fn(s->hidden_kind)
                              : (s->tile_rows_wide == 32 ? (const void *)decode_any_kernel<32, kThreads>
                                                         : (const void *)decode_any_kernel<16, kThreads>);
         uint32_t lds_bytes = 0;
@@ -374,7 +394,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
             const uint32_t lds_bytes = xdl ? s->xdl_lds_bytes[c] : s->lds_bytes[c];
             if (replan) {
                 int resident = 1;
-                if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)(xdl ? im.decode_xdl : im.decode),
+                if (hip_fail(hipOccupancyMaxActiveBlocksPerMultiprocessor(&resident, (const void *)(xdl ? im.decode_xdl[s->hidden_kind] : im.decode),
                                                                           threads, lds_bytes)) || resident < 1)
                     resident = 1;
                 s->plan[c] = plan_chunks((double)n, tiles, nw, s->n_cu, resident, xdl ? s->class_tile_us_xdl[c] : s->class_tile_us[c]);
@@ -385,7 +405,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
             a.tiles_per_chunk = pl.tiles_per_chunk;
             a.cls = c;
             a.handle_bad = 1u;
-            hipLaunchKernelGGL(xdl ? im.decode_xdl : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
+            hipLaunchKernelGGL(xdl ? im.decode_xdl[s->hidden_kind] : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
                                (hipStream_t)stream, a);
             RINR_HIP(hipGetLastError());
             launches = 1;

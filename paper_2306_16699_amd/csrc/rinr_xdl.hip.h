@@ -38,6 +38,11 @@ __host__ __device__ inline bool xdl_int_layer(uint32_t bits, float scale_pre) {
 // 16-register accumulator tuples cost more in register pressure than the issue slots give back.
 __host__ __device__ constexpr int xdl_tile_rows(int cls) { return cls == 2 ? 32 : 16; }
 
+// What kinds of hidden layer the models served by a launch have (the host knows it from the store): a kernel
+// for one kind runs a layer loop without a branch on the kind.  With the branch inside, the compiler hoists and
+// sinks the two halves' common epilogue code out of the branches, away from the MFMAs it is meant to run under.
+enum { kHiddenAllInt = 0, kHiddenAllRaw = 1, kHiddenMixed = 2 };
+
 struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
     uint32_t off_hi;       // byte offset of the fp16 operand block
     uint32_t off_lo;       // byte offset of the low-part block, 0 = none (integer layer)
@@ -292,7 +297,19 @@ __device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, co
     }
 }
 
-template <int TM, int WP>
+// One hidden layer for both halves of a 64-pixel tile, software-pipelined: the matrix work of X(l) is issued
+// together with the sine/split of Y(l-1), then the matrix work of Y(l) with the sine/split of X(l).
+template <int TM, int WP, bool LO>
+__device__ __forceinline__ void xdl_layer(XHalf<TM, WP> &X, XHalf<TM, WP> &Y, const char *lds, const XLayer el, int lane, int g,
+                                          float scale_prev, float scale, float neg1) {
+    xdl_hidden<TM, WP, LO>(X, lds, el, lane, g);
+    xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
+    __builtin_amdgcn_sched_barrier(0);
+    xdl_hidden<TM, WP, LO>(Y, lds, el, lane, g);
+    xdl_epilogue<TM, WP>(X, scale, neg1);
+}
+
+template <int TM, int WP, int MODE>
 __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, float *lds_f) {
     typedef XLayout<TM, WP> LY;
     typedef XTile<TM> T;
@@ -376,19 +393,13 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
             const XLayer el = uniform_layer(tab[l]);
             int ll = lane;                       // the lane group is derived from the lane index per layer, not kept
             asm volatile("" : "+v"(ll));
-            const int gl = ll / TM;
-            if (el.off_lo == 0) {
-                xdl_hidden<TM, WP, false>(X, lds, el, ll, gl);
-                xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
-                __builtin_amdgcn_sched_barrier(0);
-                xdl_hidden<TM, WP, false>(Y, lds, el, ll, gl);
-                xdl_epilogue<TM, WP>(X, el.scale, neg1);
+            if constexpr (MODE == kHiddenAllInt) {
+                xdl_layer<TM, WP, false>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
+            } else if constexpr (MODE == kHiddenAllRaw) {
+                xdl_layer<TM, WP, true>(X, Y, lds, el, ll, ll / TM, 1.0f, 1.0f, neg1);
             } else {
-                xdl_hidden<TM, WP, true>(X, lds, el, ll, gl);
-                xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
-                __builtin_amdgcn_sched_barrier(0);
-                xdl_hidden<TM, WP, true>(Y, lds, el, ll, gl);
-                xdl_epilogue<TM, WP>(X, el.scale, neg1);
+                if (el.off_lo == 0) xdl_layer<TM, WP, false>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
+                else xdl_layer<TM, WP, true>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
             }
             scale_prev = el.scale;
         }
@@ -456,25 +467,25 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
 }
 
 // One width class per launch (a.cls != 0) ...
-template <int CLS, int NTHREADS>
+template <int CLS, int NTHREADS, int MODE>
 __global__ __launch_bounds__(NTHREADS) void decode_xdl_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     Work w;
     if (!decode_prologue(a, w)) return;
-    xdl_body<xdl_tile_rows(CLS), 16 * CLS>(a, w, lds_f);
+    xdl_body<xdl_tile_rows(CLS), 16 * CLS, MODE>(a, w, lds_f);
 }
 
 // ... or every width class in one launch (a.cls == 0)
-template <int NTHREADS>
+template <int NTHREADS, int MODE>
 __global__ __launch_bounds__(NTHREADS) void decode_xdl_any_kernel(const DecodeArgs a) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];
     Work w;
     if (!decode_prologue(a, w)) return;
     switch (w.cls) {
-        case 1: xdl_body<xdl_tile_rows(1), 16>(a, w, lds_f); break;
-        case 2: xdl_body<xdl_tile_rows(2), 32>(a, w, lds_f); break;
-        case 3: xdl_body<xdl_tile_rows(3), 48>(a, w, lds_f); break;
-        default: xdl_body<xdl_tile_rows(4), 64>(a, w, lds_f); break;
+        case 1: xdl_body<xdl_tile_rows(1), 16, MODE>(a, w, lds_f); break;
+        case 2: xdl_body<xdl_tile_rows(2), 32, MODE>(a, w, lds_f); break;
+        case 3: xdl_body<xdl_tile_rows(3), 48, MODE>(a, w, lds_f); break;
+        default: xdl_body<xdl_tile_rows(4), 64, MODE>(a, w, lds_f); break;
     }
 }
 
