@@ -389,7 +389,16 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
         // ---- hidden layers, software-pipelined over the two halves:
         //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
         float scale_prev = 1.0f;
-        for (int l = 1; l < L - 1; ++l) {
+        int l = 1;
+        if (MODE == kHiddenAllInt && L > 2) {      // first hidden layer on its own: the first layer's outputs carry no scale
+            const XLayer el = uniform_layer(tab[1]);
+            int ll = lane;
+            asm volatile("" : "+v"(ll));
+            xdl_layer<TM, WP, false>(X, Y, lds, el, ll, ll / TM, 1.0f, el.scale, neg1);
+            scale_prev = el.scale;
+            l = 2;
+        }
+        for (; l < L - 1; ++l) {
             const XLayer el = uniform_layer(tab[l]);
             int ll = lane;                       // the lane group is derived from the lane index per layer, not kept
             asm volatile("" : "+v"(ll));
