@@ -7,7 +7,7 @@ with the packed store, the image ids and the output tensors already resident in 
 Default workload: 256 images of 224x224, MLP 2->64 (x6 sine layers)->3, 8-bit hidden
 layers, 70 % pruned, uint8 + fp32 NCHW outputs.  Data is synthetic (seeded).
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, steps, ms_per_step, config, roofline and cpu_baseline objects.
 """
 from __future__ import annotations
 
@@ -127,8 +127,8 @@ def main() -> int:
                     help="run only a plain device-to-device copy of MIB MiB per step (counter calibration) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build decodes on one GPU only (images are independent; see DESIGN.md "
-              "for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build decodes on one GPU only (images are independent: with more GPUs every rank "
+              "would decode its own slice of the batch's ids). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import torch
