@@ -10,7 +10,7 @@
 //
 // Same structure as the fp32 kernel: workgroup = (slot, range of 64-pixel tiles), model
 // expanded once into LDS, activations register-resident across layers.  Tile = TM rows x TM
-// pixels (TM = 32 for padded widths 32 and 64, else 16), lane = (n = lane % TM, g = lane / TM).
+// pixels (TM = 32 at padded width 32, and at 64 in the all-class kernel; else 16), lane = (n = lane % TM, g = lane / TM).
 // A lane's accumulator registers come in quads of four consecutive rows; quad Q (counted over
 // all row tiles of the layer) holds rows
 //     TM = 16:  16 Q + 4 g + b            TM = 32:  32 (Q / 4) + 8 (Q % 4) + 4 g + b,   b = 0..3.
