@@ -235,6 +235,34 @@ def test_decode_on_side_stream_and_preallocated_out(torch):
     st.close()
 
 
+def test_decode_replayed_from_a_captured_graph(torch):
+    """A decode call enqueues one kernel and nothing else, so it can be captured once and replayed with other
+    ids in the same buffers (tight serving loops); every replay is checked against an eager call."""
+    w = synth.workload(5, n_images=24, pool=64, H=40, W=36)          # ragged store: the all-class kernel
+    st = rinr.Store(rinr.pack(w.models))
+    rng = np.random.default_rng(5)
+    ids = ids_dev(torch, w.image_ids)
+    out = torch.empty((24, 3, 40, 36), device="cuda")
+    out8 = torch.empty((24, 3, 40, 36), dtype=torch.uint8, device="cuda")
+    st.decode_batch_ex(ids, 40, 36, rinr.OUT_F32_AND_U8, out=out, out_u8=out8)     # plans the launch before capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        st.decode_batch_ex(ids, 40, 36, rinr.OUT_F32_AND_U8, out=out, out_u8=out8)
+    for _ in range(3):
+        ids.copy_(torch.from_numpy(rng.integers(0, 64, 24).astype(np.int64)))
+        out.fill_(-3.0)
+        out8.fill_(7)
+        g.replay()
+        torch.cuda.synchronize()
+        ref, ref8 = st.decode_batch_ex(ids, 40, 36, rinr.OUT_F32_AND_U8)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref) and torch.equal(out8, ref8)
+    assert st.status() == 0
+    del g
+    st.close()
+
+
 def test_store_open_validates_on_device_copy(torch):
     w = synth.workload(2, n_images=3)
     blob = rinr.pack(w.models)
