@@ -47,10 +47,10 @@ def host_threads() -> int:
 
 # encode-side shapes: the three model shapes of Sec. VI-A at image sizes of their kind, and the headline decode model
 FIT_SHAPES = {
-    "cifar": ("3 sine layers x 15, 32x32 images", [2, 15, 15, 15, 3], 2048, 32, 32),
-    "flowers": ("9 sine layers x 32, 224x224 images", [2] + [32] * 9 + [3], 256, 224, 224),
-    "imagenet": ("9 sine layers x 40, 224x224 images", [2] + [40] * 9 + [3], 256, 224, 224),
-    "w64": ("6 sine layers x 64 (the cfg4 decode model), 224x224 images", [2] + [64] * 6 + [3], 256, 224, 224),
+    "cifar": ("3 linear layers, 15 hidden units, 32x32 images", [2, 15, 15, 3], 2048, 32, 32),
+    "flowers": ("10 linear layers, 32 hidden units, 224x224 images", [2] + [32] * 9 + [3], 256, 224, 224),
+    "imagenet": ("10 linear layers, 40 hidden units, 224x224 images", [2] + [40] * 9 + [3], 256, 224, 224),
+    "w64": ("7 linear layers, 64 hidden units (the cfg4 decode model), 224x224 images", [2] + [64] * 6 + [3], 256, 224, 224),
 }
 
 
@@ -121,6 +121,9 @@ def main() -> int:
     ap.add_argument("--augment", action="store_true",
                     help="time the decode with a per-slot affine map of the sampling grid and per-channel "
                          "normalisation fused in (fp32 output only)")
+    ap.add_argument("--paper", choices=["cifar", "flowers", "imagenet"], default=None,
+                    help="decode a batch of models of one of the paper's own shapes (Sec. VI-A) instead of --config")
+    ap.add_argument("--batch", type=int, default=0, help="batch size for --paper (default: the paper's backbone batch size)")
     ap.add_argument("--fit", choices=sorted(FIT_SHAPES), default=None,
                     help="time the encode side instead: full-batch Adam steps of the per-image fit (one JSON line of its own)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -157,7 +160,8 @@ def main() -> int:
     if args.threads:
         rinr.tune(2, args.threads)
 
-    w = synth.workload(args.config)
+    w = synth.paper_workload(args.paper, args.batch or None) if args.paper else synth.workload(args.config)
+    args.config = args.paper or args.config
     blob = rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)
     st = rinr.Store(blob)
     ids = torch.from_numpy(w.image_ids).cuda()

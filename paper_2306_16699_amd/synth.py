@@ -304,3 +304,25 @@ def init_params(seed: int, widths: Sequence[int], n: int, w0: float = 30.0) -> n
         parts.append((2 * uw - 1) * bw)
         parts.append((2 * ub - 1) * bb)
     return np.concatenate(parts, axis=1).astype(np.float32)
+
+
+# ---- decode workloads with the paper's own model shapes (Sec. VI-A) -----------------------------
+
+PAPER_SHAPES = {
+    # name: (sine layers, width, image side, batch size of the backbone run, fraction of weights kept)
+    "cifar": (2, 15, 32, 128, 1.0 - 0.156),       # "3 layers with 15 hidden dimensions", 32x32, 15.6 % pruned on average
+    "flowers": (9, 32, 224, 64, 1.0 - 0.242),     # "10 layers with 32 hidden dimensions", 24.2 % pruned
+    "imagenet": (9, 40, 224, 64, 1.0 - 0.255),    # "10 layers with 40 hidden dimensions", 25.5 % pruned
+}
+
+
+def paper_workload(name: str, n_images: Optional[int] = None, pool: int = 1024) -> Workload:
+    """A batch drawn from a pool of models of one of the paper's three shapes: 8-bit hidden layers, first and
+    last layer fp32 (Sec. IV-B), the average pruning ratio the paper reports (Sec. IV-A), coordinates on 0..1
+    (Sec. III-A).  Batch size defaults to the one of the paper's backbone runs (Sec. VI-A)."""
+    n_sine, width, side, batch, keep = PAPER_SHAPES[name]
+    n = n_images or batch
+    ms = _uniform_models(100 + len(name), pool, width, n_sine, 8, keep)
+    ids = draw_ids(100 + len(name), n, pool, False)
+    return Workload(f"paper {name}: {n}x{side}x{side} 2-{width}x{n_sine}-3 q8 keep {keep:.3f}", ms, ids, side, side, False,
+                    30.0, 0.0, 1.0)

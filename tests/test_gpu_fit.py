@@ -9,7 +9,7 @@ from paper_2306_16699_amd import rinr, rinr_fit, synth
 pytestmark = pytest.mark.gpu
 
 ARCHS = {
-    "cifar 3x15 @32x32": ([2, 15, 15, 15, 3], 32, 32),
+    "cifar 3x15 @32x32": ([2, 15, 15, 3], 32, 32),
     "flowers 10x32 ragged": ([2] + [32] * 9 + [3], 24, 20),
     "mini-imagenet 10x40 ragged": ([2] + [40] * 9 + [3], 17, 13),
     "width 64 x6": ([2] + [64] * 6 + [3], 16, 16),
