@@ -182,6 +182,15 @@ def test_paper_shaped_models(torch):
     check_workload(torch, w, models=image_like(ms), u8=True)
 
 
+@pytest.mark.parametrize("width", [5, 8, 9, 40, 41, 50, 56])
+def test_widths_around_half_a_row_tile(torch, width):
+    """Widths just below, at and above half a 16-row tile and a full one (padding rows of every amount)."""
+    ms = synth._uniform_models(31 + width, 6, width, 3, (6, 8), 0.6) + synth._uniform_models(57 + width, 2, width, 2, None, None)
+    w = synth.Workload(f"width {width}", ms, np.array([7, 0, 3, 5, 6, 1]), 21, 19, False)
+    check_workload(torch, w)
+    check_workload(torch, w, models=image_like(ms), u8=True)
+
+
 # ---- degenerate sizes ---------------------------------------------------------------------------------------
 @pytest.mark.parametrize("H,W", [(1, 1), (1, 63), (64, 1), (1, 65), (8, 8), (9, 7), (127, 1)])
 def test_small_and_ragged_grids(torch, H, W):
