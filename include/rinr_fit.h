@@ -96,9 +96,10 @@ int rinr_fit_get_params(const rinr_fit *fit, float *params, void *stream);
  * float[n_images][3][H][W], 4-byte aligned, values on the 0..1 scale of the decoded image. */
 int rinr_fit_steps(rinr_fit *fit, const float *targets, int32_t n_steps, const rinr_fit_opts *opts, void *stream);
 
-/* Loss (as defined by opts->loss_scale) and gradient at the current parameters, without an update:
+/* Loss and gradient at the current parameters, without an update:
  * grad host float[n_images][n_params] (NULL = loss only), loss host float[n_images].  For checking
- * the kernels against a reference; synchronises with `stream`. */
+ * the kernels against a reference: allocates a device gradient buffer inside the handle on first use and
+ * synchronises with `stream`.  loss_scale as in rinr_fit_opts (0 = the mean). */
 int rinr_fit_loss_grad(rinr_fit *fit, const float *targets, float loss_scale, float *loss, float *grad, void *stream);
 /* Per-image loss seen by the most recent step (before its update).  Synchronises with `stream`. */
 int rinr_fit_last_loss(const rinr_fit *fit, float *loss, void *stream);
