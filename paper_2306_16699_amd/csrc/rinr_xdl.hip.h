@@ -42,6 +42,9 @@ __host__ __device__ constexpr int xdl_tile_rows(int cls) { return cls == 2 ? 32 
 // for one kind runs a layer loop without a branch on the kind.  With the branch inside, the compiler hoists and
 // sinks the two halves' common epilogue code out of the branches, away from the MFMAs it is meant to run under.
 enum { kHiddenAllInt = 0, kHiddenAllRaw = 1, kHiddenMixed = 2 };
+// Added to the kind: activations travel as one fp16 value instead of a hi+lo pair (RINR_FLAG_FP16_ACT): one MFMA
+// term less per layer and a two-instruction epilogue, at 2^-12 relative rounding per activation.
+enum { kAct16 = 4 };
 
 struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
     uint32_t off_hi;       // byte offset of the fp16 operand block
@@ -212,6 +215,14 @@ __device__ __forceinline__ void sine_split(float d0, float d1, float d2, float d
     lo = (h4v){b0[0], b0[1], b1[0], b1[1]};
 }
 
+// sine of four accumulator values rounded to fp16 (single-term activations)
+__device__ __forceinline__ void sine_hi(float d0, float d1, float d2, float d3, float scale, h4v &hi) {
+    const f2v p0 = {sin_rev(d0 * scale), sin_rev(d1 * scale)};
+    const f2v p1 = {sin_rev(d2 * scale), sin_rev(d3 * scale)};
+    const h2v a0 = __builtin_convertvector(p0, h2v), a1 = __builtin_convertvector(p1, h2v);
+    hi = (h4v){a0[0], a0[1], a1[0], a1[1]};
+}
+
 // ---- per-wavefront state of one half (32 pixels) of a 64-pixel tile ------------------------------------
 template <int TM, int WP> struct XHalf {
     typedef XLayout<TM, WP> LY;
@@ -223,7 +234,7 @@ template <int TM, int WP> struct XHalf {
 };
 
 // sine + split of all accumulators of a half: WP/2 activations per lane, 4 VALU instructions each
-template <int TM, int WP>
+template <int TM, int WP, bool A16>
 __device__ __forceinline__ void xdl_epilogue(XHalf<TM, WP> &H, float scale, float neg1) {
     typedef XLayout<TM, WP> LY;
     constexpr int QT = LY::RV / 4;                 // quads per tile
@@ -235,20 +246,24 @@ __device__ __forceinline__ void xdl_epilogue(XHalf<TM, WP> &H, float scale, floa
             for (int qq = 0; qq < QT; ++qq) {
                 const int q = t * QT + qq;         // quad index over the layer's rows
                 h4v hi, lo;
-                sine_split(H.D[nt][t][qq * 4 + 0], H.D[nt][t][qq * 4 + 1], H.D[nt][t][qq * 4 + 2], H.D[nt][t][qq * 4 + 3], scale, neg1,
-                           hi, lo);
+                if (A16) sine_hi(H.D[nt][t][qq * 4 + 0], H.D[nt][t][qq * 4 + 1], H.D[nt][t][qq * 4 + 2], H.D[nt][t][qq * 4 + 3], scale, hi);
+                else sine_split(H.D[nt][t][qq * 4 + 0], H.D[nt][t][qq * 4 + 1], H.D[nt][t][qq * 4 + 2], H.D[nt][t][qq * 4 + 3], scale, neg1,
+                                hi, lo);
                 if (q < 2 * LY::KJ) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         H.Hh[nt][q >> 1][(q & 1) * 4 + v] = hi[v];
-                        H.Hl[nt][q >> 1][(q & 1) * 4 + v] = lo[v];
+                        if (!A16) H.Hl[nt][q >> 1][(q & 1) * 4 + v] = lo[v];
                     }
-                } else { H.Hh4[nt] = hi; H.Hl4[nt] = lo; }
+                } else {
+                    H.Hh4[nt] = hi;
+                    if (!A16) H.Hl4[nt] = lo;
+                }
             }
 }
 
-// MFMAs of one hidden layer for a half.  LO: the layer has a low weight part (three terms).
-template <int TM, int WP, bool LO>
+// MFMAs of one hidden layer for a half.  LO: the layer has a low weight part (one more term).  A16: no low activation part.
+template <int TM, int WP, bool LO, bool A16>
 __device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, const XLayer el, int lane, int g) {
     typedef XLayout<TM, WP> LY;
     typedef XTile<TM> T;
@@ -270,8 +285,10 @@ __device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, co
             if (j == 0) c = bt[mt * LY::G];
 #pragma unroll
             for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(av, H.Hh[nt][j], j == 0 ? c : H.D[nt][mt]);
+            if (!A16) {
 #pragma unroll
-            for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(av, H.Hl[nt][j], H.D[nt][mt]);
+                for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(av, H.Hl[nt][j], H.D[nt][mt]);
+            }
             if (LO) {
 #pragma unroll
                 for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma(aw, H.Hh[nt][j], H.D[nt][mt]);
@@ -287,8 +304,10 @@ __device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, co
             if (KJ == 0) c = bt[mt * LY::G];
 #pragma unroll
             for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(av, H.Hh4[nt], KJ == 0 ? c : H.D[nt][mt]);
+            if (!A16) {
 #pragma unroll
-            for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(av, H.Hl4[nt], H.D[nt][mt]);
+                for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(av, H.Hl4[nt], H.D[nt][mt]);
+            }
             if (LO) {
 #pragma unroll
                 for (int nt = 0; nt < NTH; ++nt) H.D[nt][mt] = T::mfma_half(aw, H.Hh4[nt], H.D[nt][mt]);
@@ -299,18 +318,20 @@ __device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, co
 
 // One hidden layer for both halves of a 64-pixel tile, software-pipelined: the matrix work of X(l) is issued
 // together with the sine/split of Y(l-1), then the matrix work of Y(l) with the sine/split of X(l).
-template <int TM, int WP, bool LO>
+template <int TM, int WP, bool LO, bool A16>
 __device__ __forceinline__ void xdl_layer(XHalf<TM, WP> &X, XHalf<TM, WP> &Y, const char *lds, const XLayer el, int lane, int g,
                                           float scale_prev, float scale, float neg1) {
-    xdl_hidden<TM, WP, LO>(X, lds, el, lane, g);
-    xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
+    xdl_hidden<TM, WP, LO, A16>(X, lds, el, lane, g);
+    xdl_epilogue<TM, WP, A16>(Y, scale_prev, neg1);
     __builtin_amdgcn_sched_barrier(0);
-    xdl_hidden<TM, WP, LO>(Y, lds, el, lane, g);
-    xdl_epilogue<TM, WP>(X, scale, neg1);
+    xdl_hidden<TM, WP, LO, A16>(Y, lds, el, lane, g);
+    xdl_epilogue<TM, WP, A16>(X, scale, neg1);
 }
 
-template <int TM, int WP, int MODE>
+template <int TM, int WP, int MODE_>
 __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, float *lds_f) {
+    constexpr int MODE = MODE_ & 3;
+    constexpr bool A16 = (MODE_ & kAct16) != 0;
     typedef XLayout<TM, WP> LY;
     typedef XTile<TM> T;
     typedef typename T::acc_t acc_t;
@@ -385,7 +406,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
                 }
             }
         }
-        xdl_epilogue<TM, WP>(X, 1.0f, neg1);
+        xdl_epilogue<TM, WP, A16>(X, 1.0f, neg1);
         // ---- hidden layers, software-pipelined over the two halves:
         //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
         float scale_prev = 1.0f;
@@ -394,7 +415,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
             const XLayer el = uniform_layer(tab[1]);
             int ll = lane;
             asm volatile("" : "+v"(ll));
-            xdl_layer<TM, WP, false>(X, Y, lds, el, ll, ll / TM, 1.0f, el.scale, neg1);
+            xdl_layer<TM, WP, false, A16>(X, Y, lds, el, ll, ll / TM, 1.0f, el.scale, neg1);
             scale_prev = el.scale;
             l = 2;
         }
@@ -403,16 +424,16 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
             int ll = lane;                       // the lane group is derived from the lane index per layer, not kept
             asm volatile("" : "+v"(ll));
             if constexpr (MODE == kHiddenAllInt) {
-                xdl_layer<TM, WP, false>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
+                xdl_layer<TM, WP, false, A16>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
             } else if constexpr (MODE == kHiddenAllRaw) {
-                xdl_layer<TM, WP, true>(X, Y, lds, el, ll, ll / TM, 1.0f, 1.0f, neg1);
+                xdl_layer<TM, WP, true, A16>(X, Y, lds, el, ll, ll / TM, 1.0f, 1.0f, neg1);
             } else {
-                if (el.off_lo == 0) xdl_layer<TM, WP, false>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
-                else xdl_layer<TM, WP, true>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
+                if (el.off_lo == 0) xdl_layer<TM, WP, false, A16>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
+                else xdl_layer<TM, WP, true, A16>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
             }
             scale_prev = el.scale;
         }
-        xdl_epilogue<TM, WP>(Y, scale_prev, neg1);
+        xdl_epilogue<TM, WP, A16>(Y, scale_prev, neg1);
         asm volatile("" : "+s"(ones));           // pixel indices and addresses: derived again rather than kept
         lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
         const int go = lane / TM, no = lane % TM;
@@ -433,9 +454,8 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
 #pragma unroll
                 for (int nt = 0; nt < 2 * NTH; ++nt) {
                     const h8v bh = nt < NTH ? X.Hh[nt % NTH][j] : Y.Hh[nt % NTH][j];
-                    const h8v bl = nt < NTH ? X.Hl[nt % NTH][j] : Y.Hl[nt % NTH][j];
                     O[nt] = T::mfma(av, bh, O[nt]);
-                    O[nt] = T::mfma(av, bl, O[nt]);
+                    if (!A16) O[nt] = T::mfma(av, nt < NTH ? X.Hl[nt % NTH][j] : Y.Hl[nt % NTH][j], O[nt]);
                     O[nt] = T::mfma(aw, bh, O[nt]);
                 }
             }
@@ -444,9 +464,8 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
 #pragma unroll
                 for (int nt = 0; nt < 2 * NTH; ++nt) {
                     const h4v bh = nt < NTH ? X.Hh4[nt % NTH] : Y.Hh4[nt % NTH];
-                    const h4v bl = nt < NTH ? X.Hl4[nt % NTH] : Y.Hl4[nt % NTH];
                     O[nt] = T::mfma_half(av, bh, O[nt]);
-                    O[nt] = T::mfma_half(av, bl, O[nt]);
+                    if (!A16) O[nt] = T::mfma_half(av, nt < NTH ? X.Hl4[nt % NTH] : Y.Hl4[nt % NTH], O[nt]);
                     O[nt] = T::mfma_half(aw, bh, O[nt]);
                 }
             }

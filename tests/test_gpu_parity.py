@@ -42,8 +42,11 @@ def image_like(models):
     return out
 
 
+WORST = {}       # largest unclamped error seen per mode, printed at the end of the run
+
+
 def check_workload(torch, w, models=None, tile=DEFAULT_TILE, u8=False):
-    """Both matrix paths (default split-precision fp16 MFMA, and fp32 MFMA) against the oracle."""
+    """All three precisions (default split-precision fp16 MFMA, fp32 MFMA, single-fp16 activations) against the oracle."""
     models = models if models is not None else w.models
     rinr.tune(0, tile)
     try:
@@ -54,11 +57,12 @@ def check_workload(torch, w, models=None, tile=DEFAULT_TILE, u8=False):
     ref_nc = oracle.decode(models, w.image_ids, w.H, w.W, w.w0, w.coord_lo, w.coord_hi, clamp=False)
     ref, ref8 = oracle.decode(models, w.image_ids, w.H, w.W, w.w0, w.coord_lo, w.coord_hi, want_u8=True)
     worst = 0.0
-    for mode in (0, rinr.FLAG_FP32_MFMA):
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT):
         got_nc = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy().astype(np.float64)
         err_nc = np.abs(got_nc - ref_nc).max()
         assert err_nc <= TOL, f"mode {mode}: unclamped max-abs {err_nc}"
         worst = max(worst, err_nc)
+        WORST[mode] = max(WORST.get(mode, 0.0), err_nc)
         got = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode).cpu().numpy()
         assert got.min() >= 0.0 and got.max() <= 1.0
         assert np.abs(got.astype(np.float64) - ref).max() <= TOL
@@ -327,3 +331,7 @@ def test_decode_argument_errors(torch):
     assert L.rinr_debug_dequant(h, 0, 9, out.data_ptr(), None, None) == rinr.E_ARG
     assert L.rinr_store_open(st.dev_blob.data_ptr() + 4, None, 64, C.byref(C.c_void_p())) == rinr.E_ALIGN
     st.close()
+
+
+def test_zz_report_worst_errors():
+    print("largest unclamped max-abs error per mode:", {("default" if m == 0 else "fp32 MFMA" if m == rinr.FLAG_FP32_MFMA else "fp16 activations"): f"{e:.2e}" for m, e in WORST.items()})
