@@ -131,10 +131,12 @@ enum { RINR_FLAG_NO_CLAMP = 1,     /* fp32 output only: write the linear output 
        RINR_FLAG_FP16_ACT = 8 };   /* faster, less precise: activations travel between layers as one
                                       fp16 value (relative rounding 2^-12 each) instead of a hi+lo
                                       pair; weights, coordinates and accumulation as in the default
-                                      kernel.  Measured max-abs error against the fp64 definition on
-                                      the benchmark workloads: 2e-5 .. 4e-4, inside the 1e-3
-                                      tolerance; the error grows with the output layer's gain.
-                                      Ignored together with RINR_FLAG_FP32_MFMA                    */
+                                      kernel.  Measured max-abs error against the fp64 definition:
+                                      2e-5 .. 5e-5 on the benchmark workloads, up to 5.5e-4 on the
+                                      test models; it grows with depth and with the output layer's
+                                      gain and has no model-independent bound.  Ignored together
+                                      with RINR_FLAG_FP32_MFMA, and where the store is served by the
+                                      fp32 kernels anyway (operands beyond fp16 range)            */
 
 /* Augmentation on the GPU, fused into the decode (Sec. III-B: decoded images are augmented
  * on the GPU before they reach the backbone).  Geometric augmentation (flip, crop + resize,
