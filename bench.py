@@ -49,7 +49,7 @@ def host_threads() -> int:
 # encode-side shapes: the three model shapes of Sec. VI-A at image sizes of their kind, and the headline decode model
 FIT_SHAPES = {
     "cifar": ("3 linear layers, 15 hidden units, 32x32 images", [2, 15, 15, 3], 2048, 32, 32),
-    "flowers": ("10 linear layers, 32 hidden units, 224x224 images", [2] + [32] * 9 + [3], 256, 224, 224),
+    "flowers": ("10 linear layers, 32 hidden units, 224x224 images", [2] + [32] * 9 + [3], 512, 224, 224),   # two images per CU
     "imagenet": ("10 linear layers, 40 hidden units, 224x224 images", [2] + [40] * 9 + [3], 256, 224, 224),
     "w64": ("7 linear layers, 64 hidden units (the cfg4 decode model), 224x224 images", [2] + [64] * 6 + [3], 256, 224, 224),
 }
@@ -60,6 +60,7 @@ def bench_fit(args) -> int:
     import torch
     from paper_2306_16699_amd import rinr_fit, synth
     what, widths, n, H, W = FIT_SHAPES[args.fit]
+    n = args.batch or n
     base = torch.from_numpy(synth.images(1, 8, H, W)).cuda()
     tgt = base.repeat((n + 7) // 8, 1, 1, 1)[:n].contiguous()
     f = rinr_fit.Fit(widths, n, H, W)
@@ -126,7 +127,7 @@ def main() -> int:
                          "normalisation fused in (fp32 output only)")
     ap.add_argument("--paper", choices=["cifar", "flowers", "imagenet"], default=None,
                     help="decode a batch of models of one of the paper's own shapes (Sec. VI-A) instead of --config")
-    ap.add_argument("--batch", type=int, default=0, help="batch size for --paper (default: the paper's backbone batch size)")
+    ap.add_argument("--batch", type=int, default=0, help="batch size for --paper (default: the paper's backbone batch size) or number of images for --fit")
     ap.add_argument("--fit", choices=sorted(FIT_SHAPES), default=None,
                     help="time the encode side instead: full-batch Adam steps of the per-image fit (one JSON line of its own)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",

@@ -27,9 +27,18 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxL = RINR_FIT_MAX_LAYERS;
-// wavefronts per workgroup (= per image): 8, but 4 at widths <= 16, whose 4 tiles per layer do not feed 8 wavefronts,
-// so that three images share a CU and fill each other's barrier waits (3 x 15 on 32 x 32 images: 0.65 -> 0.43 ms per step)
-constexpr int fit_waves(int cls) { return cls == 1 ? 4 : 8; }
+// Wavefronts per workgroup (= per image).  Every phase between two barriers is a short dependent chain per
+// wavefront, so what fills the matrix pipe is other wavefronts: 4 at widths <= 16, whose 4 tiles per layer do not feed
+// more, and several images per CU; 8 at widths <= 32, two images per CU; 12 at width 48, one wavefront per tile of its
+// 12-tile layers (LDS holds one image); 8 at width 64.
+constexpr int fit_waves(int cls) { return cls == 1 ? 4 : (cls == 3 ? 12 : 8); }
+// Wavefronts per SIMD the kernel is compiled for (the register budget follows): at widths <= 32 two workgroups
+// share a CU (10 x 32 at 224 x 224, 512 images: 26.8 -> 20.3 ms per step).
+constexpr int fit_waves_per_simd(int cls) { return cls == 1 ? 3 : (cls == 2 ? 4 : (cls == 3 ? 3 : 2)); }
+// Layer counts the kernels are built for, per class: the accumulators of all layers stay in registers, so the depth
+// is a compile-time bound and a shallow model takes the kernel with the smaller one.
+constexpr int fit_depth_lo(int cls) { return cls == 1 ? 4 : (cls == 2 ? 10 : (cls == 3 ? 10 : 7)); }
+constexpr int fit_depth_hi(int cls) { return cls <= 2 ? kMaxL : fit_depth_lo(cls); }
 constexpr uint32_t kLdsLimit = 160 * 1024;
 
 thread_local int g_fit_last_hip = 0;
@@ -43,27 +52,35 @@ inline bool hip_fail(hipError_t e) {
 // Shapes of one width class (hidden widths padded to DP = 16 * CLS) and the LDS layout in floats.
 // Padding is with zero weights, which leaves values and gradients of the real entries unchanged (a padded unit
 // outputs sin(0) = 0 and receives no error), so every hidden layer has the same compile-time shape whatever
-// its true width.  Pixels are taken 64 at a time.  Row strides are odd so that strided operand reads spread
-// over the banks.
+// its true width.  Pixels are taken 64 at a time.
+// LDS has 32 banks and serves a wavefront's 4-byte accesses in two halves of 32 lanes; a half that hits a bank
+// twice takes a second cycle.  The MFMA operands are read in two patterns, lane (m, kq) -> (row m, column kq) and
+// -> (row kq, column m), so a half covers 16 rows x 2 columns or 2 rows x 16 columns.  Weight rows have stride
+// LD = 2 * odd, which makes the first pattern conflict-free.  Pixel-buffer rows come in pairs: row r starts at
+// prow(r) = (r / 2) * PAIR + (r % 2) * ODD with PAIR = 2 * odd and ODD = 16 (mod 32), so that 16 consecutive rows
+// start in 16 different even banks and the two rows of a pair are 16 banks apart: both patterns conflict-free.
+// (At width 64 the pair layout does not fit the deepest model into LDS; there rows keep the plain stride 65.)
 //   W0  [DP][5]        first layer: columns x, y, bias, 0
 //   Wh  [DP][LD] each  layers 1..L-2: columns 0..DP-1 weights, DP bias, then zeros
 //   Wl  [16][LD]       last layer (3 real rows)
-//   B0, B1, B2 [KP][PS] three pixel buffers.  Forward: the input of layer l is B[l & 1] (rows 0..DP-1
+//   B0, B1, B2 [KP rows] three pixel buffers.  Forward: the input of layer l is B[l & 1] (rows 0..DP-1
 //       activations, row DP ones, rest zero; layer 0: rows x, y, ones, zero).  Backward: B0 holds the restored
 //       input of the layer at hand, B1 / B2 the back-propagated error, ping-pong.
 // Pre-activations are not stashed in LDS: the wavefront that computed a tile keeps it in registers until the
 // backward pass has used it (sine again for the weight gradient's operand, cosine for the error).
 template <int CLS> struct Shape {
-    static constexpr int PC = 64, PS = PC + 1, PT = PC / 16;
-    static constexpr int DP = 16 * CLS, MT = CLS, LD = DP + 5, KP = DP + 4, KS = KP / 4;
+    static constexpr int PC = 64, PT = PC / 16;
+    static constexpr int DP = 16 * CLS, MT = CLS, LD = DP + 6, KP = DP + 4, KS = KP / 4;
+    static constexpr int PAIR = CLS <= 3 ? 162 : 130, ODD = CLS <= 3 ? 80 : 65;
+    static __host__ __device__ constexpr int prow(int r) { return (r >> 1) * PAIR + (r & 1) * ODD; }
     static constexpr int NIT = MT + 1;                              // column tiles of a hidden weight gradient (bias column included)
-    static constexpr int ML = CLS == 4 ? 7 : (CLS == 3 ? 10 : kMaxL);   // deepest model: register budget (and LDS at width 64)
+    static constexpr int ML = fit_depth_hi(CLS);                    // deepest model: register budget (and LDS at width 64)
     static constexpr int NW = fit_waves(CLS), NTHREADS = NW * 64;
     static constexpr int ZSLOTS = (MT * PT + NW - 1) / NW;  // forward tiles a wavefront owns per layer
     static constexpr int GSLOTS = (MT * NIT + NW - 1) / NW; // gradient tiles a wavefront owns per layer
     static __host__ __device__ constexpr int w_off(int l) { return l == 0 ? 0 : DP * 5 + (l - 1) * DP * LD; }
     static __host__ __device__ constexpr int w_end(int L) { return DP * 5 + (L - 2) * DP * LD + 16 * LD; }
-    static __host__ __device__ constexpr int buf(int b, int L) { return w_end(L) + b * KP * PS; }
+    static __host__ __device__ constexpr int buf(int b, int L) { return w_end(L) + b * prow(KP); }
     static __host__ __device__ constexpr int total(int L) { return buf(3, L); }
 };
 
@@ -116,11 +133,12 @@ __device__ __forceinline__ int param_index(const FitArgs &a, int l, int o, int i
     return -1;
 }
 
-template <int CLS>
-__global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const FitArgs a) {
+template <int CLS, int ML>
+__global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void fit_step_kernel(const FitArgs a) {
     typedef Shape<CLS> S;
-    constexpr int DP = S::DP, MT = S::MT, LD = S::LD, KP = S::KP, KS = S::KS, PC = S::PC, PS = S::PS, PT = S::PT, NIT = S::NIT;
-    constexpr int ML = S::ML, ZSLOTS = S::ZSLOTS, GSLOTS = S::GSLOTS, kWaves = S::NW, kThreads = S::NTHREADS;
+    constexpr int DP = S::DP, MT = S::MT, LD = S::LD, KP = S::KP, KS = S::KS, PC = S::PC, PT = S::PT, NIT = S::NIT;
+    constexpr int PSTEP = 2 * S::PAIR;       // prow(r + 4) - prow(r): one k-step down a pixel buffer
+    constexpr int ZSLOTS = S::ZSLOTS, GSLOTS = S::GSLOTS, kWaves = S::NW, kThreads = S::NTHREADS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ float red[kWaves];
     const int tid = threadIdx.x;
@@ -142,7 +160,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
         for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + e % din] = src[e];
         for (int o = tid; o < dout; o += kThreads) Wt[o * ld + bias_col] = src[dout * din + o];
     }
-    for (int p = tid; p < PC; p += kThreads) B0[DP * PS + p] = B1[DP * PS + p] = 1.0f;
+    for (int p = tid; p < PC; p += kThreads) B0[S::prow(DP) + p] = B1[S::prow(DP) + p] = 1.0f;
     __syncthreads();
 
     f32x4 acc[ML][GSLOTS];          // weight-gradient tiles, whole step
@@ -163,10 +181,10 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
             uint32_t p = c * PC + tid;
             p = p < a.HW ? p : a.HW - 1;
             const uint32_t row = p / a.W, col = p - row * a.W;
-            B0[tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
-            B0[PS + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
-            B0[2 * PS + tid] = 1.0f;
-            B0[3 * PS + tid] = 0.0f;
+            B0[S::prow(0) + tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
+            B0[S::prow(1) + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
+            B0[S::prow(2) + tid] = 1.0f;
+            B0[S::prow(3) + tid] = 0.0f;
         }
     };
 
@@ -189,13 +207,13 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
                         const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
                         f32x4 z;
                         if (l == 0)
-                            z = contract<1, 4, 4 * PS>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, in + kq * PS + col, true, zero4);
+                            z = contract<1, 4, PSTEP>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, in + S::prow(kq) + col, true, zero4);
                         else
-                            z = contract<KS, 4, 4 * PS>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + kq * PS + col, true, zero4);
+                            z = contract<KS, 4, PSTEP>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + S::prow(kq) + col, true, zero4);
                         if (!last) {
                             zst[l][s] = z;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) out[(mt * 16 + 4 * kq + v) * PS + col] = __builtin_amdgcn_sinf(z[v] * a.w0rev);
+                            for (int v = 0; v < 4; ++v) out[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(z[v] * a.w0rev);
                         } else {
                             const uint32_t pix = c * PC + col;
 #pragma unroll
@@ -204,7 +222,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
                                 float e = 0.0f;
                                 if (o < 3 && pix < a.HW) e = z[v] - a.target[(img * 3 + o) * a.HW + pix];
                                 loss_part = fmaf(e, e, loss_part);
-                                B2[o * PS + col] = 2.0f * a.loss_scale * e;
+                                B2[S::prow(o) + col] = 2.0f * a.loss_scale * e;
                             }
                         }
                     }
@@ -228,7 +246,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
                         if (task < MT * PT) {
                             const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) B0[(mt * 16 + 4 * kq + v) * PS + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v] * a.w0rev);
+                            for (int v = 0; v < 4; ++v) B0[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v] * a.w0rev);
                         }
                     }
                 }
@@ -237,7 +255,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
 #pragma unroll
                     for (int s = 0; s < GSLOTS; ++s) {
                         const int ot = wave + s * kWaves;
-                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, B0 + (m < 4 ? m : 0) * PS + kq, m < 4, acc[0][s]);
+                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(m < 4 ? m : 0) + kq, m < 4, acc[0][s]);
                     }
                 } else {
                     const int ntasks = (last ? 1 : MT) * NIT;
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
                         if (task < ntasks) {
                             const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
                             const bool live = i < KP;
-                            acc[l][s] = contract<PC / 4, 4, 4>(Dc + (ot * 16 + m) * PS + kq, B0 + (live ? i : 0) * PS + kq, live, acc[l][s]);
+                            acc[l][s] = contract<PC / 4, 4, 4>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(live ? i : 0) + kq, live, acc[l][s]);
                         }
                     }
                     const float *Wt = lds + S::w_off(l);
@@ -256,11 +274,11 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
                         const int task = wave + s * kWaves;
                         if (task < MT * PT) {
                             const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
-                            const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + kq * PS + col;
-                            const f32x4 g = last ? contract<4, 4 * LD, 4 * PS>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, 4 * PS>(ap, bp, true, zero4);
+                            const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + S::prow(kq) + col;
+                            const f32x4 g = last ? contract<4, 4 * LD, PSTEP>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, PSTEP>(ap, bp, true, zero4);
 #pragma unroll
                             for (int v = 0; v < 4; ++v)
-                                Dn[(it * 16 + 4 * kq + v) * PS + col] = g[v] * a.w0 * __builtin_amdgcn_cosf(zst[l - 1][s][v] * a.w0rev);
+                                Dn[S::prow(it * 16 + 4 * kq + v) + col] = g[v] * a.w0 * __builtin_amdgcn_cosf(zst[l - 1][s][v] * a.w0rev);
                         }
                     }
                 }
@@ -322,12 +340,16 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS) void fit_step_kernel(const Fi
 
 typedef void (*fit_fn)(const FitArgs);
 
-fit_fn kernel_for(int cls) {
+template <int CLS> fit_fn kernel_of(int L) {
+    if (L <= fit_depth_lo(CLS)) return fit_step_kernel<CLS, fit_depth_lo(CLS)>;
+    return fit_step_kernel<CLS, fit_depth_hi(CLS)>;
+}
+fit_fn kernel_for(int cls, int L) {
     switch (cls) {
-        case 1: return fit_step_kernel<1>;
-        case 2: return fit_step_kernel<2>;
-        case 3: return fit_step_kernel<3>;
-        default: return fit_step_kernel<4>;
+        case 1: return kernel_of<1>(L);
+        case 2: return kernel_of<2>(L);
+        case 3: return kernel_of<3>(L);
+        default: return kernel_of<4>(L);
     }
 }
 // LDS floats of a model of L linear layers in width class cls, or 0 if the class's kernel is not built that deep
@@ -393,7 +415,7 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
         hip_fail(hipMalloc((void **)&f->loss, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
         hip_fail(hipMemset(f->params, 0, np * 4)) || hip_fail(hipMemset(f->m, 0, np * 4)) ||
         hip_fail(hipMemset(f->v, 0, np * 4)) || hip_fail(hipMemset(f->loss, 0, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
-        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->cls), hipFuncAttributeMaxDynamicSharedMemorySize,
+        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->cls, arch->n_layers), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)kLdsLimit - 256))) {
         rinr_fit_destroy(f);
         return RINR_E_HIP;
@@ -503,7 +525,7 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.L = f->arch.n_layers;
     for (int l = 0; l <= a.L; ++l) a.d[l] = f->arch.widths[l];
     for (int l = 0; l < a.L; ++l) a.p_off[l] = f->p_off[l];
-    hipLaunchKernelGGL(kernel_for(f->cls), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->cls)), (size_t)f->lds_floats * 4, stream, a);
+    hipLaunchKernelGGL(kernel_for(f->cls, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->cls)), (size_t)f->lds_floats * 4, stream, a);
     FIT_HIP(hipGetLastError());
     return RINR_OK;
 }

@@ -14,6 +14,8 @@ ARCHS = {
     "mini-imagenet 10x40 ragged": ([2] + [40] * 9 + [3], 17, 13),
     "width 64 x6": ([2] + [64] * 6 + [3], 16, 16),
     "tapered": ([2, 24, 48, 32, 3], 9, 31),
+    "narrow, 6 layers": ([2] + [12] * 5 + [3], 11, 9),             # the deep kernel of the width-16 class
+    "12 layers x 20": ([2] + [20] * 11 + [3], 10, 10),            # the deep kernel of the width-32 class, the API's depth limit
     "one hidden unit": ([2, 1, 3], 5, 7),
     "one pixel": ([2, 8, 3], 1, 1),
 }
