@@ -8,6 +8,11 @@
 //     forward        Z_l [d_out x PC]  = W_l [d_out x d_in+1] . H_l [d_in+1 x PC]        H_{l+1} = sin(w0 Z_l)
 //     weight grads   dW_l [d_out x d_in+1] += D_l [d_out x PC] . H_l^T                   (contraction over pixels)
 //     backward       D_{l-1} = (W_l^T . D_l) * w0 cos(w0 Z_{l-1})
+// In LDS the sine layers' weights and biases are held times w0 / 2pi, so that Z comes out in revolutions, the unit of
+// the hardware sine and cosine, and the error is carried as E_l = c_l D_l with c_{L-1} = 1, c_{L-2} = 1 / w0,
+// c_{l-1} = c_l / 2pi below that: then E_{l-1} = (W_l^T . E_l) * cos(2pi Z'_{l-1}) with the LDS weights, one multiply per
+// element, and the accumulated sum over pixels of E_l H_l^T is c_l times the gradient: the factor 1 / c_l is applied
+// once per parameter at the end.
 // The weight-gradient tiles stay in registers for the whole step (each wavefront owns a fixed set of
 // tiles of every layer), so gradients never touch memory: at the end of the step the owner of an entry
 // applies Adam to it in place.  Nothing is allocated and nothing leaves the workgroup except the
@@ -98,6 +103,7 @@ struct FitArgs {
     int32_t L;
     int32_t d[kMaxL + 1];         // true widths
     int32_t p_off[kMaxL];         // offset of W_l in the parameter vector
+    float gscale[kMaxL];          // what the accumulated weight gradient of layer l is multiplied by (see the kernel)
 };
 
 __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
@@ -105,8 +111,9 @@ __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) { return __bui
 // acc += sum over KSTEPS k-steps of A(ks) x B(ks): one float per lane from LDS at ap[ks * AS], bp[ks * BS].
 // Trip count and strides are compile-time, so the loads become immediate-offset reads issued ahead of the MFMAs
 // (in groups of eight, which bounds the registers held).
-template <int KSTEPS, int AS, int BS>
-__device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, bool live, f32x4 acc) {
+// ZERO: the sum starts at 0 (as the first MFMA's inline-constant C operand: no registers are cleared).
+template <int KSTEPS, int AS, int BS, bool ZERO>
+__device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, f32x4 acc) {
 #pragma unroll
     for (int k0 = 0; k0 < KSTEPS; k0 += 8) {
         constexpr int G = 8;
@@ -115,11 +122,11 @@ __device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, bool
         for (int u = 0; u < G; ++u)
             if (k0 + u < KSTEPS) {
                 av[u] = ap[(k0 + u) * AS];
-                bv[u] = live ? bp[(k0 + u) * BS] : 0.0f;
+                bv[u] = bp[(k0 + u) * BS];
             }
 #pragma unroll
         for (int u = 0; u < G; ++u)
-            if (k0 + u < KSTEPS) acc = mfma4(av[u], bv[u], acc);
+            if (k0 + u < KSTEPS) acc = mfma4(av[u], bv[u], (ZERO && k0 + u == 0) ? (f32x4){0.0f, 0.0f, 0.0f, 0.0f} : acc);
     }
     return acc;
 }
@@ -157,8 +164,9 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
         const int din = a.d[l], dout = a.d[l + 1], ld = l == 0 ? 5 : LD, bias_col = l == 0 ? 2 : DP;
         float *Wt = lds + S::w_off(l);
         const float *src = P + a.p_off[l];
-        for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + e % din] = src[e];
-        for (int o = tid; o < dout; o += kThreads) Wt[o * ld + bias_col] = src[dout * din + o];
+        const float sc = l < L - 1 ? a.w0rev : 1.0f;
+        for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + e % din] = src[e] * sc;
+        for (int o = tid; o < dout; o += kThreads) Wt[o * ld + bias_col] = src[dout * din + o] * sc;
     }
     for (int p = tid; p < PC; p += kThreads) B0[S::prow(DP) + p] = B1[S::prow(DP) + p] = 1.0f;
     __syncthreads();
@@ -190,6 +198,10 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
 
     const uint32_t nchunks = (a.HW + PC - 1) / PC;
     for (uint32_t c = 0; c < nchunks; ++c) {
+        // the layer count is read afresh per chunk: otherwise every "l < L" and "l == L - 1" of the unrolled layers is
+        // kept as a lane mask across the loop, and the masks spill out of the scalar registers
+        int L = a.L;
+        asm volatile("" : "+s"(L));
         put_coords(c);
         __syncthreads();
         // ---- forward: Z_l = W_l H_l, one 16x16 tile (rows mt, pixels nt) per task; H_{l+1} = sin(w0 Z_l)
@@ -207,13 +219,13 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
                         f32x4 z;
                         if (l == 0)
-                            z = contract<1, 4, PSTEP>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, in + S::prow(kq) + col, true, zero4);
+                            z = contract<1, 4, PSTEP, true>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, in + S::prow(kq) + col, zero4);
                         else
-                            z = contract<KS, 4, PSTEP>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + S::prow(kq) + col, true, zero4);
+                            z = contract<KS, 4, PSTEP, true>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + S::prow(kq) + col, zero4);
                         if (!last) {
                             zst[l][s] = z;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) out[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(z[v] * a.w0rev);
+                            for (int v = 0; v < 4; ++v) out[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(z[v]);
                         } else {
                             const uint32_t pix = c * PC + col;
 #pragma unroll
@@ -246,7 +258,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         if (task < MT * PT) {
                             const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) B0[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v] * a.w0rev);
+                            for (int v = 0; v < 4; ++v) B0[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v]);
                         }
                     }
                 }
@@ -255,7 +267,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
 #pragma unroll
                     for (int s = 0; s < GSLOTS; ++s) {
                         const int ot = wave + s * kWaves;
-                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(m < 4 ? m : 0) + kq, m < 4, acc[0][s]);
+                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(m < 4 ? m : 3) + kq, acc[0][s]);   // row 3 is zero
                     }
                 } else {
                     const int ntasks = (last ? 1 : MT) * NIT;
@@ -264,8 +276,8 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         const int task = wave + s * kWaves;
                         if (task < ntasks) {
                             const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
-                            const bool live = i < KP;
-                            acc[l][s] = contract<PC / 4, 4, 4>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(live ? i : 0) + kq, live, acc[l][s]);
+                            // columns beyond the bias column read one of the buffer's zero rows
+                            acc[l][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(i < KP ? i : DP + 1) + kq, acc[l][s]);
                         }
                     }
                     const float *Wt = lds + S::w_off(l);
@@ -275,10 +287,10 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         if (task < MT * PT) {
                             const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
                             const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + S::prow(kq) + col;
-                            const f32x4 g = last ? contract<4, 4 * LD, PSTEP>(ap, bp, true, zero4) : contract<DP / 4, 4 * LD, PSTEP>(ap, bp, true, zero4);
+                            const f32x4 g = last ? contract<4, 4 * LD, PSTEP, true>(ap, bp, zero4) : contract<DP / 4, 4 * LD, PSTEP, true>(ap, bp, zero4);
 #pragma unroll
                             for (int v = 0; v < 4; ++v)
-                                Dn[S::prow(it * 16 + 4 * kq + v) + col] = g[v] * a.w0 * __builtin_amdgcn_cosf(zst[l - 1][s][v] * a.w0rev);
+                                Dn[S::prow(it * 16 + 4 * kq + v) + col] = g[v] * __builtin_amdgcn_cosf(zst[l - 1][s][v]);
                         }
                     }
                 }
@@ -318,7 +330,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         const int at = param_index(a, l, ot * 16 + 4 * kq + v, it * 16 + m, bias_col);
                         if (at >= 0) {
                             const bool kept = !K || K[at];
-                            const float g = kept ? acc[l][s][v] : 0.0f;
+                            const float g = kept ? acc[l][s][v] * a.gscale[l] : 0.0f;
                             if (G) {
                                 G[at] = g;
                             } else if (kept) {
@@ -518,6 +530,14 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.w0 = f->arch.w0;
     a.w0rev = (float)((double)f->arch.w0 / (2.0 * 3.14159265358979323846));
     a.loss_scale = loss_scale;
+    {
+        const int L = f->arch.n_layers;
+        double c = 1.0;                                   // 1 / c_l
+        for (int l = L - 1; l >= 0; --l) {
+            a.gscale[l] = (float)c;
+            c = l == L - 1 ? (double)f->arch.w0 : c * 2.0 * 3.14159265358979323846;
+        }
+    }
     a.lr = lr;
     a.c1inv = (float)(1.0 / (1.0 - std::pow((double)b1, (double)t)));
     a.c2inv = (float)(1.0 / (1.0 - std::pow((double)b2, (double)t)));
