@@ -63,8 +63,8 @@ inline bool hip_fail(hipError_t e) {
 // -> (row kq, column m), so a half covers 16 rows x 2 columns or 2 rows x 16 columns.  Weight rows have stride
 // LD = 2 * odd, which makes the first pattern conflict-free.  Pixel-buffer rows come in pairs: row r starts at
 // prow(r) = (r / 2) * PAIR + (r % 2) * ODD with PAIR = 2 * odd and ODD = 16 (mod 32), so that 16 consecutive rows
-// start in 16 different even banks and the two rows of a pair are 16 banks apart: both patterns conflict-free.
-// (At width 64 the pair layout does not fit the deepest model into LDS; there rows keep the plain stride 65.)
+// start in 16 different even banks and the two rows of a pair are 16 banks apart: both patterns conflict-free
+// (ODD = 80 is the first such value that holds 64 pixels, PAIR = 146 the first that holds two rows).
 //   W0  [DP][5]        first layer: columns x, y, bias, 0
 //   Wh  [DP][LD] each  layers 1..L-2: columns 0..DP-1 weights, DP bias, then zeros
 //   Wl  [16][LD]       last layer (3 real rows)
@@ -76,7 +76,7 @@ inline bool hip_fail(hipError_t e) {
 template <int CLS> struct Shape {
     static constexpr int PC = 64, PT = PC / 16;
     static constexpr int DP = 16 * CLS, MT = CLS, LD = DP + 6, KP = DP + 4, KS = KP / 4;
-    static constexpr int PAIR = CLS <= 3 ? 162 : 130, ODD = CLS <= 3 ? 80 : 65;
+    static constexpr int PAIR = 146, ODD = 80;
     static __host__ __device__ constexpr int prow(int r) { return (r >> 1) * PAIR + (r & 1) * ODD; }
     static constexpr int NIT = MT + 1;                              // column tiles of a hidden weight gradient (bias column included)
     static constexpr int ML = fit_depth_hi(CLS);                    // deepest model: register budget (and LDS at width 64)
