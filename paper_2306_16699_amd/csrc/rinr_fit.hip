@@ -32,18 +32,21 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxL = RINR_FIT_MAX_LAYERS;
+// The kernels are built per hidden width rounded up to a multiple of 8 (WQ) and per depth bucket.
+// Row tiles of a hidden layer: MT = ceil(WQ / 16).
+constexpr int fit_tiles(int wq) { return (wq + 15) / 16; }
 // Wavefronts per workgroup (= per image).  Every phase between two barriers is a short dependent chain per
 // wavefront, so what fills the matrix pipe is other wavefronts: 4 at widths <= 16, whose 4 tiles per layer do not feed
-// more, and several images per CU; 8 at widths <= 32, two images per CU; 12 at width 48, one wavefront per tile of its
-// 12-tile layers (LDS holds one image); 8 at width 64.
-constexpr int fit_waves(int cls) { return cls == 1 ? 4 : (cls == 3 ? 12 : 8); }
+// more, and several images per CU; 8 at widths <= 32, two images per CU; 12 at widths <= 48, one wavefront per tile of
+// their 12-tile layers (LDS holds one image); 8 above.
+constexpr int fit_waves(int wq) { return fit_tiles(wq) == 1 ? 4 : (fit_tiles(wq) == 3 ? 12 : 8); }
 // Wavefronts per SIMD the kernel is compiled for (the register budget follows): at widths <= 32 two workgroups
 // share a CU (10 x 32 at 224 x 224, 512 images: 26.8 -> 20.3 ms per step).
-constexpr int fit_waves_per_simd(int cls) { return cls == 1 ? 3 : (cls == 2 ? 4 : (cls == 3 ? 3 : 2)); }
-// Layer counts the kernels are built for, per class: the accumulators of all layers stay in registers, so the depth
+constexpr int fit_waves_per_simd(int wq) { return fit_tiles(wq) == 1 ? 3 : (fit_tiles(wq) == 2 ? 4 : (fit_tiles(wq) == 3 ? 3 : 2)); }
+// Layer counts the kernels are built for: the accumulators of all layers stay in registers, so the depth
 // is a compile-time bound and a shallow model takes the kernel with the smaller one.
-constexpr int fit_depth_lo(int cls) { return cls == 1 ? 4 : (cls == 2 ? 10 : (cls == 3 ? 10 : 7)); }
-constexpr int fit_depth_hi(int cls) { return cls <= 2 ? kMaxL : fit_depth_lo(cls); }
+constexpr int fit_depth_lo(int wq) { return fit_tiles(wq) == 1 ? 4 : (fit_tiles(wq) == 4 ? 7 : 10); }
+constexpr int fit_depth_hi(int wq) { return fit_tiles(wq) <= 2 ? kMaxL : fit_depth_lo(wq); }
 constexpr uint32_t kLdsLimit = 160 * 1024;
 
 thread_local int g_fit_last_hip = 0;
@@ -54,10 +57,12 @@ inline bool hip_fail(hipError_t e) {
 }
 #define FIT_HIP(call) do { if (hip_fail(call)) return RINR_E_HIP; } while (0)
 
-// Shapes of one width class (hidden widths padded to DP = 16 * CLS) and the LDS layout in floats.
-// Padding is with zero weights, which leaves values and gradients of the real entries unchanged (a padded unit
-// outputs sin(0) = 0 and receives no error), so every hidden layer has the same compile-time shape whatever
-// its true width.  Pixels are taken 64 at a time.
+// Shapes for hidden widths <= WQ (a multiple of 8) and the LDS layout in floats.  Padding is with zero weights, which
+// leaves values and gradients of the real entries unchanged (a padded unit outputs sin(0) = 0 and receives no
+// error), so every hidden layer has the same compile-time shape whatever its true width.  Pixels are taken 64 at a time.
+// A layer's input is a block of four rows (ones, and three rows whose weights are zero) followed by the activations:
+// the bias is the weight of the row of ones, the contraction over the inputs takes 1 + WQ / 4 k-steps of four rows, and
+// what lies beyond row 4 + WQ is never read.  The first layer's block is (ones, x, y, zero) and is its whole input.
 // LDS has 32 banks and serves a wavefront's 4-byte accesses in two halves of 32 lanes; a half that hits a bank
 // twice takes a second cycle.  The MFMA operands are read in two patterns, lane (m, kq) -> (row m, column kq) and
 // -> (row kq, column m), so a half covers 16 rows x 2 columns or 2 rows x 16 columns.  Weight rows have stride
@@ -65,27 +70,29 @@ inline bool hip_fail(hipError_t e) {
 // prow(r) = (r / 2) * PAIR + (r % 2) * ODD with PAIR = 2 * odd and ODD = 16 (mod 32), so that 16 consecutive rows
 // start in 16 different even banks and the two rows of a pair are 16 banks apart: both patterns conflict-free
 // (ODD = 80 is the first such value that holds 64 pixels, PAIR = 146 the first that holds two rows).
-//   W0  [DP][5]        first layer: columns x, y, bias, 0
-//   Wh  [DP][LD] each  layers 1..L-2: columns 0..DP-1 weights, DP bias, then zeros
+//   W0  [RO][6]        first layer: columns bias, x, y, 0
+//   Wh  [RO][LD] each  layers 1..L-2: columns bias, 0, 0, 0, then the weights (RO = 16 MT rows, zero beyond the width)
 //   Wl  [16][LD]       last layer (3 real rows)
-//   B0, B1, B2 [KP rows] three pixel buffers.  Forward: the input of layer l is B[l & 1] (rows 0..DP-1
-//       activations, row DP ones, rest zero; layer 0: rows x, y, ones, zero).  Backward: B0 holds the restored
-//       input of the layer at hand, B1 / B2 the back-propagated error, ping-pong.
+//   B0, B1, B2 [KR rows] three pixel buffers.  Forward: the input of layer l is B[l & 1] (row 0 ones, rows 4.. the
+//       activations; B0 rows 1..3 hold x, y, 0).  Backward: B0 holds the restored input of the layer at hand; B1 / B2
+//       the back-propagated error with row = unit, ping-pong (so B1's row of ones is written again for every chunk).
 // Pre-activations are not stashed in LDS: the wavefront that computed a tile keeps it in registers until the
 // backward pass has used it (sine again for the weight gradient's operand, cosine for the error).
-template <int CLS> struct Shape {
+template <int WQ> struct Shape {
     static constexpr int PC = 64, PT = PC / 16;
-    static constexpr int DP = 16 * CLS, MT = CLS, LD = DP + 6, KP = DP + 4, KS = KP / 4;
+    static constexpr int MT = fit_tiles(WQ), RO = 16 * MT, LD = RO + 6, KR = RO + 4;
+    static constexpr int KSF = 1 + WQ / 4;                          // k-steps of a hidden layer's forward contraction
+    static constexpr int KSB = WQ / 4;                              // ... of the backward one (over the layer's outputs)
+    static constexpr int NIT = (4 + WQ + 15) / 16;                  // column tiles of a hidden weight gradient (block of four + inputs)
     static constexpr int PAIR = 146, ODD = 80;
     static __host__ __device__ constexpr int prow(int r) { return (r >> 1) * PAIR + (r & 1) * ODD; }
-    static constexpr int NIT = MT + 1;                              // column tiles of a hidden weight gradient (bias column included)
-    static constexpr int ML = fit_depth_hi(CLS);                    // deepest model: register budget (and LDS at width 64)
-    static constexpr int NW = fit_waves(CLS), NTHREADS = NW * 64;
+    static constexpr int ML = fit_depth_hi(WQ);                     // deepest model: register budget (and LDS at width 64)
+    static constexpr int NW = fit_waves(WQ), NTHREADS = NW * 64;
     static constexpr int ZSLOTS = (MT * PT + NW - 1) / NW;  // forward tiles a wavefront owns per layer
     static constexpr int GSLOTS = (MT * NIT + NW - 1) / NW; // gradient tiles a wavefront owns per layer
-    static __host__ __device__ constexpr int w_off(int l) { return l == 0 ? 0 : DP * 5 + (l - 1) * DP * LD; }
-    static __host__ __device__ constexpr int w_end(int L) { return DP * 5 + (L - 2) * DP * LD + 16 * LD; }
-    static __host__ __device__ constexpr int buf(int b, int L) { return w_end(L) + b * prow(KP); }
+    static __host__ __device__ constexpr int w_off(int l) { return l == 0 ? 0 : RO * 6 + (l - 1) * RO * LD; }
+    static __host__ __device__ constexpr int w_end(int L) { return RO * 6 + (L - 2) * RO * LD + 16 * LD; }
+    static __host__ __device__ constexpr int buf(int b, int L) { return w_end(L) + b * prow(KR); }
     static __host__ __device__ constexpr int total(int L) { return buf(3, L); }
 };
 
@@ -132,18 +139,20 @@ __device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, f32x
 }
 
 // Where entry (o, i) of layer l's weight-gradient tile lives in the parameter vector, or -1 (padding).
-__device__ __forceinline__ int param_index(const FitArgs &a, int l, int o, int i, int bias_col) {
+// Column 0 is the bias; input j is column 1 + j of the first layer and column 4 + j of the others.
+__device__ __forceinline__ int param_index(const FitArgs &a, int l, int o, int i) {
     const int din = a.d[l], dout = a.d[l + 1];
     if (o >= dout) return -1;
-    if (i < din) return a.p_off[l] + o * din + i;
-    if (i == bias_col) return a.p_off[l] + dout * din + o;
+    if (i == 0) return a.p_off[l] + dout * din + o;
+    const int j = i - (l == 0 ? 1 : 4);
+    if (j >= 0 && j < din) return a.p_off[l] + o * din + j;
     return -1;
 }
 
-template <int CLS, int ML>
-__global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void fit_step_kernel(const FitArgs a) {
-    typedef Shape<CLS> S;
-    constexpr int DP = S::DP, MT = S::MT, LD = S::LD, KP = S::KP, KS = S::KS, PC = S::PC, PT = S::PT, NIT = S::NIT;
+template <int WQ, int ML>
+__global__ __launch_bounds__(Shape<WQ>::NTHREADS, fit_waves_per_simd(WQ)) void fit_step_kernel(const FitArgs a) {
+    typedef Shape<WQ> S;
+    constexpr int MT = S::MT, LD = S::LD, KR = S::KR, KSF = S::KSF, KSB = S::KSB, PC = S::PC, PT = S::PT, NIT = S::NIT;
     constexpr int PSTEP = 2 * S::PAIR;       // prow(r + 4) - prow(r): one k-step down a pixel buffer
     constexpr int ZSLOTS = S::ZSLOTS, GSLOTS = S::GSLOTS, kWaves = S::NW, kThreads = S::NTHREADS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -151,24 +160,22 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, m = lane & 15, kq = lane >> 4;
-    const int L = a.L;
     const size_t img = blockIdx.x;
     float *P = a.params + img * a.n_params;
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    float *const B0 = lds + S::buf(0, L), *const B1 = lds + S::buf(1, L), *const B2 = lds + S::buf(2, L);
+    float *const B0 = lds + S::buf(0, a.L), *const B1 = lds + S::buf(1, a.L), *const B2 = lds + S::buf(2, a.L);
 
-    // ---- set up: zero everything, weights with the bias as an extra column, rows of ones
-    for (int q = tid; q < S::total(L); q += kThreads) lds[q] = 0.0f;
+    // ---- set up: zero everything, then the weights (sine layers times w0 / 2pi) behind their bias column
+    for (int q = tid; q < S::total(a.L); q += kThreads) lds[q] = 0.0f;
     __syncthreads();
-    for (int l = 0; l < L; ++l) {
-        const int din = a.d[l], dout = a.d[l + 1], ld = l == 0 ? 5 : LD, bias_col = l == 0 ? 2 : DP;
+    for (int l = 0; l < a.L; ++l) {
+        const int din = a.d[l], dout = a.d[l + 1], ld = l == 0 ? 6 : LD, first = l == 0 ? 1 : 4;
         float *Wt = lds + S::w_off(l);
         const float *src = P + a.p_off[l];
-        const float sc = l < L - 1 ? a.w0rev : 1.0f;
-        for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + e % din] = src[e] * sc;
-        for (int o = tid; o < dout; o += kThreads) Wt[o * ld + bias_col] = src[dout * din + o] * sc;
+        const float sc = l < a.L - 1 ? a.w0rev : 1.0f;
+        for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + first + e % din] = src[e] * sc;
+        for (int o = tid; o < dout; o += kThreads) Wt[o * ld] = src[dout * din + o] * sc;
     }
-    for (int p = tid; p < PC; p += kThreads) B0[S::prow(DP) + p] = B1[S::prow(DP) + p] = 1.0f;
     __syncthreads();
 
     f32x4 acc[ML][GSLOTS];          // weight-gradient tiles, whole step
@@ -182,16 +189,16 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
     }
     float loss_part = 0.0f;
 
-    // pixel-centre coordinates of the chunk into rows x, y, ones, zero of B0 (a ragged last chunk repeats the
-    // last pixel; its error is zeroed)
+    // rows ones, x, y, zero of B0: the first layer's input at the chunk's pixel centres (a ragged last chunk
+    // repeats the last pixel; its error is zeroed)
     auto put_coords = [&](uint32_t c) {
         if (tid < PC) {
             uint32_t p = c * PC + tid;
             p = p < a.HW ? p : a.HW - 1;
             const uint32_t row = p / a.W, col = p - row * a.W;
-            B0[S::prow(0) + tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
-            B0[S::prow(1) + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
-            B0[S::prow(2) + tid] = 1.0f;
+            B0[S::prow(0) + tid] = 1.0f;
+            B0[S::prow(1) + tid] = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, a.lo);
+            B0[S::prow(2) + tid] = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, a.lo);
             B0[S::prow(3) + tid] = 0.0f;
         }
     };
@@ -203,8 +210,9 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
         int L = a.L;
         asm volatile("" : "+s"(L));
         put_coords(c);
+        if (tid >= kThreads - PC) B1[S::prow(0) + tid - (kThreads - PC)] = 1.0f;     // the backward pass kept errors here
         __syncthreads();
-        // ---- forward: Z_l = W_l H_l, one 16x16 tile (rows mt, pixels nt) per task; H_{l+1} = sin(w0 Z_l)
+        // ---- forward: Z_l = W_l H_l, one 16x16 tile (rows mt, pixels nt) per task; H_{l+1} = sin(2pi Z_l)
 #pragma unroll
         for (int l = 0; l < ML; ++l) {
             if (l < L) {
@@ -219,13 +227,13 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
                         f32x4 z;
                         if (l == 0)
-                            z = contract<1, 4, PSTEP, true>(lds + S::w_off(0) + (mt * 16 + m) * 5 + kq, in + S::prow(kq) + col, zero4);
+                            z = contract<1, 4, PSTEP, true>(lds + S::w_off(0) + (mt * 16 + m) * 6 + kq, in + S::prow(kq) + col, zero4);
                         else
-                            z = contract<KS, 4, PSTEP, true>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + S::prow(kq) + col, zero4);
+                            z = contract<KSF, 4, PSTEP, true>(lds + S::w_off(l) + (mt * 16 + m) * LD + kq, in + S::prow(kq) + col, zero4);
                         if (!last) {
                             zst[l][s] = z;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) out[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(z[v]);
+                            for (int v = 0; v < 4; ++v) out[S::prow(4 + mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(z[v]);
                         } else {
                             const uint32_t pix = c * PC + col;
 #pragma unroll
@@ -242,8 +250,8 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                 __syncthreads();
             }
         }
-        // ---- backward, layer by layer: restore H_l into B0; then dW_l += D_l H_l^T into this wavefront's
-        //      accumulators (tile rows ot, columns it) and D_{l-1} = (W_l^T D_l) * w0 cos(w0 z_{l-1}) (tile rows it, pixels nt)
+        // ---- backward, layer by layer: restore H_l into B0; then dW_l += E_l H_l^T into this wavefront's
+        //      accumulators (tile rows ot, columns it) and E_{l-1} = (W_l^T E_l) * cos(2pi z_{l-1}) (tile rows it, pixels nt)
         float *Dc = B2, *Dn = B1;
 #pragma unroll
         for (int l = ML - 1; l >= 0; --l) {
@@ -258,7 +266,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         if (task < MT * PT) {
                             const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) B0[S::prow(mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v]);
+                            for (int v = 0; v < 4; ++v) B0[S::prow(4 + mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v]);
                         }
                     }
                 }
@@ -266,8 +274,8 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                 if (l == 0) {
 #pragma unroll
                     for (int s = 0; s < GSLOTS; ++s) {
-                        const int ot = wave + s * kWaves;
-                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(m < 4 ? m : 3) + kq, acc[0][s]);   // row 3 is zero
+                        const int ot = wave + s * kWaves;        // columns ones, x, y; the other lanes read the zero row
+                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(m < 4 ? m : 3) + kq, acc[0][s]);
                     }
                 } else {
                     const int ntasks = (last ? 1 : MT) * NIT;
@@ -276,8 +284,8 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         const int task = wave + s * kWaves;
                         if (task < ntasks) {
                             const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
-                            // columns beyond the bias column read one of the buffer's zero rows
-                            acc[l][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(i < KP ? i : DP + 1) + kq, acc[l][s]);
+                            // columns beyond the buffer's rows read B0's zero row
+                            acc[l][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(i < KR ? i : 3) + kq, acc[l][s]);
                         }
                     }
                     const float *Wt = lds + S::w_off(l);
@@ -286,8 +294,8 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                         const int task = wave + s * kWaves;
                         if (task < MT * PT) {
                             const int it = task / PT, nt = task - it * PT, col = nt * 16 + m;
-                            const float *ap = Wt + kq * LD + it * 16 + m, *bp = Dc + S::prow(kq) + col;
-                            const f32x4 g = last ? contract<4, 4 * LD, PSTEP, true>(ap, bp, zero4) : contract<DP / 4, 4 * LD, PSTEP, true>(ap, bp, zero4);
+                            const float *ap = Wt + kq * LD + 4 + it * 16 + m, *bp = Dc + S::prow(kq) + col;
+                            const f32x4 g = last ? contract<1, 4 * LD, PSTEP, true>(ap, bp, zero4) : contract<KSB, 4 * LD, PSTEP, true>(ap, bp, zero4);
 #pragma unroll
                             for (int v = 0; v < 4; ++v)
                                 Dn[S::prow(it * 16 + 4 * kq + v) + col] = g[v] * __builtin_amdgcn_cosf(zst[l - 1][s][v]);
@@ -301,6 +309,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
             }
         }
     }
+    const int L = a.L;
 
     // ---- loss of this step's parameters
     for (int off = 32; off > 0; off >>= 1) loss_part += __shfl_xor(loss_part, off, 64);
@@ -319,7 +328,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
 #pragma unroll
     for (int l = 0; l < ML; ++l) {
         if (l < L) {
-            const int nit = l == 0 ? 1 : NIT, ntasks = (l == L - 1 ? 1 : MT) * nit, bias_col = l == 0 ? 2 : DP;
+            const int nit = l == 0 ? 1 : NIT, ntasks = (l == L - 1 ? 1 : MT) * nit;
 #pragma unroll
             for (int s = 0; s < GSLOTS; ++s) {
                 const int task = wave + s * kWaves;
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
                     const int ot = task / nit, it = task - ot * nit;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int at = param_index(a, l, ot * 16 + 4 * kq + v, it * 16 + m, bias_col);
+                        const int at = param_index(a, l, ot * 16 + 4 * kq + v, it * 16 + m);
                         if (at >= 0) {
                             const bool kept = !K || K[at];
                             const float g = kept ? acc[l][s][v] * a.gscale[l] : 0.0f;
@@ -352,25 +361,35 @@ __global__ __launch_bounds__(Shape<CLS>::NTHREADS, fit_waves_per_simd(CLS)) void
 
 typedef void (*fit_fn)(const FitArgs);
 
-template <int CLS> fit_fn kernel_of(int L) {
-    if (L <= fit_depth_lo(CLS)) return fit_step_kernel<CLS, fit_depth_lo(CLS)>;
-    return fit_step_kernel<CLS, fit_depth_hi(CLS)>;
+template <int WQ> fit_fn kernel_of(int L) {
+    if (L <= fit_depth_lo(WQ)) return fit_step_kernel<WQ, fit_depth_lo(WQ)>;
+    return fit_step_kernel<WQ, fit_depth_hi(WQ)>;
 }
-fit_fn kernel_for(int cls, int L) {
-    switch (cls) {
-        case 1: return kernel_of<1>(L);
-        case 2: return kernel_of<2>(L);
-        case 3: return kernel_of<3>(L);
-        default: return kernel_of<4>(L);
+// wq: the widest hidden layer rounded up to a multiple of 8
+fit_fn kernel_for(int wq, int L) {
+    switch (wq) {
+        case 8: return kernel_of<8>(L);
+        case 16: return kernel_of<16>(L);
+        case 24: return kernel_of<24>(L);
+        case 32: return kernel_of<32>(L);
+        case 40: return kernel_of<40>(L);
+        case 48: return kernel_of<48>(L);
+        case 56: return kernel_of<56>(L);
+        default: return kernel_of<64>(L);
     }
 }
-// LDS floats of a model of L linear layers in width class cls, or 0 if the class's kernel is not built that deep
-int lds_floats(int cls, int L) {
-    switch (cls) {
-        case 1: return L <= Shape<1>::ML ? Shape<1>::total(L) : 0;
-        case 2: return L <= Shape<2>::ML ? Shape<2>::total(L) : 0;
-        case 3: return L <= Shape<3>::ML ? Shape<3>::total(L) : 0;
-        default: return L <= Shape<4>::ML ? Shape<4>::total(L) : 0;
+template <int WQ> int lds_floats_of(int L) { return L <= Shape<WQ>::ML ? Shape<WQ>::total(L) : 0; }
+// LDS floats of a model of L linear layers at rounded width wq, or 0 if no kernel is built that deep
+int lds_floats(int wq, int L) {
+    switch (wq) {
+        case 8: return lds_floats_of<8>(L);
+        case 16: return lds_floats_of<16>(L);
+        case 24: return lds_floats_of<24>(L);
+        case 32: return lds_floats_of<32>(L);
+        case 40: return lds_floats_of<40>(L);
+        case 48: return lds_floats_of<48>(L);
+        case 56: return lds_floats_of<56>(L);
+        default: return lds_floats_of<64>(L);
     }
 }
 
@@ -380,7 +399,7 @@ struct rinr_fit {
     rinr_fit_arch arch;
     int64_t n_images, n_params;
     int32_t H, W;
-    int PC, cls, lds_floats;
+    int PC, wq, lds_floats;     // wq: widest hidden layer rounded up to a multiple of 8
     int32_t p_off[kMaxL];
     float *params, *m, *v, *loss, *scratch_grad;
     uint8_t *keep;            // null until set
@@ -408,8 +427,8 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
     f->PC = 0;
     int wmax = 1;
     for (int l = 1; l < arch->n_layers; ++l) wmax = arch->widths[l] > wmax ? arch->widths[l] : wmax;
-    f->cls = (wmax + 15) / 16;
-    f->lds_floats = lds_floats(f->cls, arch->n_layers);
+    f->wq = (wmax + 7) / 8 * 8;
+    f->lds_floats = lds_floats(f->wq, arch->n_layers);
     if (f->lds_floats == 0 || (size_t)f->lds_floats * 4 + 256 > kLdsLimit) { delete f; return RINR_E_UNSUPPORTED; }
     f->PC = 64;
     f->n_params = 0;
@@ -427,7 +446,7 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
         hip_fail(hipMalloc((void **)&f->loss, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
         hip_fail(hipMemset(f->params, 0, np * 4)) || hip_fail(hipMemset(f->m, 0, np * 4)) ||
         hip_fail(hipMemset(f->v, 0, np * 4)) || hip_fail(hipMemset(f->loss, 0, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
-        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->cls, arch->n_layers), hipFuncAttributeMaxDynamicSharedMemorySize,
+        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->wq, arch->n_layers), hipFuncAttributeMaxDynamicSharedMemorySize,
                                      (int)kLdsLimit - 256))) {
         rinr_fit_destroy(f);
         return RINR_E_HIP;
@@ -545,7 +564,7 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.L = f->arch.n_layers;
     for (int l = 0; l <= a.L; ++l) a.d[l] = f->arch.widths[l];
     for (int l = 0; l < a.L; ++l) a.p_off[l] = f->p_off[l];
-    hipLaunchKernelGGL(kernel_for(f->cls, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->cls)), (size_t)f->lds_floats * 4, stream, a);
+    hipLaunchKernelGGL(kernel_for(f->wq, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->wq)), (size_t)f->lds_floats * 4, stream, a);
     FIT_HIP(hipGetLastError());
     return RINR_OK;
 }

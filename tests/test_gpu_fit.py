@@ -16,6 +16,8 @@ ARCHS = {
     "tapered": ([2, 24, 48, 32, 3], 9, 31),
     "narrow, 6 layers": ([2] + [12] * 5 + [3], 11, 9),             # the deep kernel of the width-16 class
     "12 layers x 20": ([2] + [20] * 11 + [3], 10, 10),            # the deep kernel of the width-32 class, the API's depth limit
+    "width 20": ([2, 20, 20, 3], 13, 11),                          # widths round up to 8: 24 ...
+    "widths 50, 56": ([2, 50, 56, 50, 3], 10, 9),                 # ... and 56
     "one hidden unit": ([2, 1, 3], 5, 7),
     "one pixel": ([2, 8, 3], 1, 1),
 }
