@@ -200,6 +200,73 @@ def test_bias_period():
     assert np.allclose(a, b, rtol=0, atol=1e-13)
 
 
+# ---- deep, rectangular chains (2 -> 5 -> 7 -> 6 -> 4 -> 3): facts that hold whatever the weights are
+def _deep_chain(rng, scale=1.0):
+    widths = [2, 5, 7, 6, 4, 3]
+    ws = [rng.uniform(-.4, .4, (widths[k + 1], widths[k])) * scale for k in range(5)]
+    bs = [rng.uniform(-.1, .1, widths[k + 1]) * scale for k in range(5)]
+    return ws, bs
+
+
+def _model(ws, bs):
+    return Model([raw_layer(w, b) for w, b in zip(ws, bs)])
+
+
+@pytest.mark.parametrize("dec", [oracle.decode, oracle_np.decode])
+def test_hidden_units_can_be_renumbered(dec):
+    """Permuting the units of a hidden layer (its rows and bias, the next layer's columns) changes nothing:
+    fails if a layer is read transposed or a bias is attached to the wrong unit, at any depth."""
+    rng = np.random.default_rng(11)
+    ws, bs = _deep_chain(rng)
+    ref = dec([_model(ws, bs)], [0], 4, 3, clamp=False)
+    for k in range(4):
+        perm = rng.permutation(ws[k].shape[0])
+        w2, b2 = [w.copy() for w in ws], [b.copy() for b in bs]
+        w2[k], b2[k], w2[k + 1] = ws[k][perm], bs[k][perm], ws[k + 1][:, perm]
+        assert np.allclose(dec([_model(w2, b2)], [0], 4, 3, clamp=False), ref, rtol=0, atol=1e-11), k     # the order of the sums changes: rounding, times w0 per layer
+
+
+@pytest.mark.parametrize("dec", [oracle.decode, oracle_np.decode])
+def test_sine_is_odd_in_every_hidden_layer(dec):
+    """Negating a unit's incoming weights and bias and its outgoing weights changes nothing (sin(-t) = -sin t):
+    fails if a hidden layer's activation is not an odd function (cosine, or a bias added after the sine)."""
+    rng = np.random.default_rng(12)
+    ws, bs = _deep_chain(rng)
+    ref = dec([_model(ws, bs)], [0], 3, 5, clamp=False)
+    for k in range(4):
+        j = int(rng.integers(ws[k].shape[0]))
+        w2, b2 = [w.copy() for w in ws], [b.copy() for b in bs]
+        w2[k][j] *= -1; b2[k][j] *= -1; w2[k + 1][:, j] *= -1
+        assert np.allclose(dec([_model(w2, b2)], [0], 3, 5, clamp=False), ref, rtol=0, atol=1e-14), k
+    # the output layer is linear: negating an output row and its bias negates that channel
+    w2, b2 = [w.copy() for w in ws], [b.copy() for b in bs]
+    w2[4][1] *= -1; b2[4][1] *= -1
+    out = dec([_model(w2, b2)], [0], 3, 5, clamp=False)
+    assert np.allclose(out[:, 1], -ref[:, 1], rtol=0, atol=1e-14) and np.allclose(out[:, 0], ref[:, 0], rtol=0, atol=1e-14)
+
+
+@pytest.mark.parametrize("dec", [oracle.decode, oracle_np.decode])
+def test_small_signal_limit_is_the_matrix_chain(dec):
+    """With arguments t = w0 z of size <= 2e-3 everywhere, sin t = t up to a relative t^2 / 6 <= 7e-7 per layer: the deep
+    model is then the affine chain out = W4 w0 (W3 w0 (... w0 (W0 x + b0) ...) + b3) + b4, evaluated here with
+    plain matrix algebra.  Fixes layer order, operand orientation and where w0 and the biases enter, at depth."""
+    rng = np.random.default_rng(13)
+    ws, bs = _deep_chain(rng, scale=1e-4)
+    ws = [w.astype(np.float32).astype(np.float64) for w in ws]
+    bs = [b.astype(np.float32).astype(np.float64) for b in bs]
+    H, W = 3, 4
+    out = dec([_model(ws, bs)], [0], H, W, clamp=False)
+    for i in range(H):
+        for j in range(W):
+            h = np.array([px(j, W), px(i, H)])
+            for k in range(4):
+                h = W0 * (ws[k] @ h + bs[k])
+                assert np.abs(h).max() < 2e-3
+            want = ws[4] @ h + bs[4]
+            assert np.allclose(out[0, :, i, j], want, rtol=0, atol=np.abs(want).max() * 1e-5 + 1e-12)
+            assert np.abs(want - bs[4]).max() > 1e-9        # the chain's contribution is visible at this tolerance
+
+
 # ---- uint8 conversion: nearest, monotone, exact at the ends
 def test_uint8_rounding_properties():
     vals = np.array([0.0, 1.0, 0.5, 1 / 255, 0.5 / 255 + 1e-9, 0.5 / 255 - 1e-9, 2.5 / 255, 3.5 / 255, 0.999], np.float64)
