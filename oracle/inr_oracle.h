@@ -15,9 +15,11 @@
  * Pins (tests marked "not gpu"): dequant against exact rational arithmetic;
  * pruned == code-at-zero-point; single-sine-layer closed form in multiprecision;
  * all-zero weights; zero first layer; axis/grid ramp; resolution nesting;
- * hand-unrolled 2x2; bias periodicity; uint8 rounding properties; and agreement
- * with a second numpy implementation.  A random full-depth MLP has no printed
- * reference value in the paper: beyond those pins it is "parity unpinned".
+ * hand-unrolled 2x2; bias periodicity; uint8 rounding properties; at depth (a
+ * rectangular five-layer chain) renumbering of hidden units, oddness of the
+ * activation and the small-signal limit against the affine matrix chain; and
+ * agreement with a second numpy implementation.  The paper prints no decoded
+ * value for any model, so none of the pins is a value from the paper.
  */
 #ifndef INR_ORACLE_H
 #define INR_ORACLE_H
