@@ -115,6 +115,35 @@ int rinr_fit_last_loss(const rinr_fit *fit, float *loss, void *stream);
 int rinr_psnr_batch(const float *a, const float *b, int64_t n_images, int64_t elems, float peak, float *psnr,
                     void *stream);
 
+/* ---- the whole encode procedure of Sec. IV in one call ----------------------------------- */
+
+typedef struct {
+    int32_t schedule;      /* PSNR-driven pruning round: 0 = Eq. 2, 1 = Eq. 3, 2 = Eq. 4 (rinr_prune_ratio)      */
+    float first_ratio;     /* fixed ratio of the first pruning round (Sec. IV-A: 0.2 for the large-image sets);
+                              0 = no first round (Sec. IV-A: the small-image set goes straight to the second)    */
+    int32_t fit_steps;     /* steps of the initial fit                                                           */
+    int32_t refit_steps;   /* steps of the re-fit after each pruning round                                       */
+    float lr, refit_lr;    /* learning rates of the fit and of the re-fits ("a smaller learning rate",
+                              Sec. IV-A), each cosine-decayed to 0 over its stage                                */
+    int32_t hidden_bits;   /* code width of the hidden layers: 8 (Sec. IV-B), 2..8 or 16; 0 = keep them fp32     */
+} rinr_encode_opts;
+
+/* Upper bound of the blob rinr_encode_images writes for this handle's images (masks present, every weight kept). */
+int rinr_encode_blob_bound(const rinr_fit *fit, int32_t hidden_bits, size_t *bytes);
+
+/* Fit (Eq. 1), prune by magnitude at first_ratio and re-fit, prune at the ratio each image's PSNR selects (Eq. 2-4;
+ * the ratio is the fraction of all entries pruned afterwards) and re-fit, quantise the hidden layers per layer
+ * (Sec. IV-B), and pack every image's model into one blob for rinr_store_open.  Nothing but a sequence of the calls
+ * above and of rinr_pack: the same steps issued one by one give the same bytes.
+ * fit: a handle whose parameters are set (rinr_fit_set_params); its keep flags are replaced, its parameters end as the
+ * final fp32 fit.  targets: device, as for rinr_fit_steps.  psnr (host float[n_images], may be NULL): PSNR in dB of that
+ * final fit before quantisation, from the mean squared error over the 0..1 range.  blob: host, `capacity` bytes
+ * (rinr_encode_blob_bound is always enough); *blob_bytes = bytes written.  RINR_E_SIZE if the blob does not fit (then
+ * *blob_bytes is the size needed and the fit has been done).  Synchronises with `stream` several times; allocates
+ * host memory proportional to n_images * n_params. */
+int rinr_encode_images(rinr_fit *fit, const float *targets, const rinr_encode_opts *opts, float *psnr, void *blob,
+                       size_t capacity, size_t *blob_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

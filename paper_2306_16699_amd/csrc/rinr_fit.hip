@@ -656,3 +656,177 @@ extern "C" int rinr_psnr_batch(const float *a, const float *b, int64_t n_images,
     FIT_HIP(hipGetLastError());
     return RINR_OK;
 }
+
+// ---- Sec. IV as one call: fit, prune (fixed round, then the PSNR-driven one), re-fit, quantise, pack -------------
+namespace {
+
+struct EncodeModels {                       // host-side model descriptions of every image, in rinr_pack's terms
+    std::vector<float> params;              // [n][n_params]
+    std::vector<uint8_t> keep;              // [n][n_params] (biases: 1)
+    std::vector<uint8_t> maskbits, codes8;
+    std::vector<uint16_t> codes16;
+    std::vector<rinr_layer_desc> layers;
+    std::vector<rinr_model_desc> models;
+};
+
+// keep flags of every weight matrix of every image after pruning `ratio[i]` of image i's entries by magnitude
+int prune_round(const rinr_fit *f, const std::vector<float> &params, const std::vector<double> &ratio, std::vector<uint8_t> &keep,
+                bool have_keep) {
+    const int L = f->arch.n_layers;
+    std::vector<uint8_t> out;
+    for (int64_t i = 0; i < f->n_images; ++i) {
+        const float *p = params.data() + (size_t)i * (size_t)f->n_params;
+        uint8_t *k = keep.data() + (size_t)i * (size_t)f->n_params;
+        for (int l = 0; l < L; ++l) {
+            const int64_t nw = (int64_t)f->arch.widths[l] * f->arch.widths[l + 1];
+            out.resize((size_t)nw);
+            const int rc = rinr_l1_mask(p + f->p_off[l], nw, ratio[(size_t)i], have_keep ? k + f->p_off[l] : nullptr, out.data());
+            if (rc) return rc;
+            std::memcpy(k + f->p_off[l], out.data(), (size_t)nw);
+        }
+    }
+    return RINR_OK;
+}
+
+int psnr_now(rinr_fit *f, const float *targets, std::vector<double> &psnr, void *stream) {
+    std::vector<float> loss((size_t)f->n_images);
+    const int rc = rinr_fit_loss_grad(f, targets, 0.0f, loss.data(), nullptr, stream);      // mean squared error
+    if (rc) return rc;
+    psnr.resize(loss.size());
+    for (size_t i = 0; i < loss.size(); ++i) psnr[i] = loss[i] > 0.0f ? -10.0 * std::log10((double)loss[i]) : INFINITY;
+    return RINR_OK;
+}
+
+int check_encode_opts(const rinr_encode_opts *o) {
+    if (!o) return RINR_E_NULL;
+    if (o->schedule < 0 || o->schedule > 2 || o->fit_steps < 0 || o->refit_steps < 0) return RINR_E_ARG;
+    if (!(o->first_ratio >= 0.0f && o->first_ratio <= 1.0f) || !(o->lr > 0.0f) || !(o->refit_lr > 0.0f)) return RINR_E_ARG;
+    if (!(o->hidden_bits == 0 || (o->hidden_bits >= 2 && o->hidden_bits <= 8) || o->hidden_bits == 16)) return RINR_E_ARG;
+    return RINR_OK;
+}
+
+// descriptions for rinr_pack: hidden layers as codes of `bits` bits, first and last layer fp32 (Sec. IV-B)
+int describe(const rinr_fit *f, int bits, EncodeModels &e) {
+    const int L = f->arch.n_layers;
+    const int64_t n = f->n_images;
+    size_t wtot = 0, mtot = 0;
+    for (int l = 0; l < L; ++l) {
+        const size_t nw = (size_t)f->arch.widths[l] * (size_t)f->arch.widths[l + 1];
+        wtot += nw;
+        mtot += (nw + 7) / 8;
+    }
+    e.maskbits.assign((size_t)n * mtot, 0);
+    if (bits && bits <= 8) e.codes8.assign((size_t)n * wtot, 0);
+    if (bits == 16) e.codes16.assign((size_t)n * wtot, 0);
+    e.layers.resize((size_t)n * (size_t)L);
+    e.models.resize((size_t)n);
+    std::vector<uint16_t> codes;
+    for (int64_t i = 0; i < n; ++i) {
+        const float *p = e.params.data() + (size_t)i * (size_t)f->n_params;
+        const uint8_t *k = e.keep.data() + (size_t)i * (size_t)f->n_params;
+        size_t woff = 0, moff = 0;
+        for (int l = 0; l < L; ++l) {
+            const int din = f->arch.widths[l], dout = f->arch.widths[l + 1];
+            const size_t nw = (size_t)din * (size_t)dout;
+            uint8_t *mb = e.maskbits.data() + (size_t)i * mtot + moff;
+            for (size_t q = 0; q < nw; ++q)
+                if (k[f->p_off[l] + q]) mb[q >> 3] |= (uint8_t)(1u << (q & 7));
+            rinr_layer_desc &d = e.layers[(size_t)i * (size_t)L + (size_t)l];
+            d.in = din;
+            d.out = dout;
+            d.bits = 0;
+            d.scale = 1.0f;
+            d.zp = 0;
+            d.weights = p + f->p_off[l];
+            d.mask = mb;
+            d.bias = p + f->p_off[l] + nw;
+            if (bits && l > 0 && l < L - 1) {
+                codes.resize(nw);
+                const int rc = rinr_quantize_layer(p + f->p_off[l], k + f->p_off[l], (int64_t)nw, bits, &d.scale, &d.zp, codes.data());
+                if (rc) return rc;
+                d.bits = bits;
+                if (bits <= 8) {
+                    uint8_t *c8 = e.codes8.data() + (size_t)i * wtot + woff;
+                    for (size_t q = 0; q < nw; ++q) c8[q] = (uint8_t)codes[q];
+                    d.weights = c8;
+                } else {
+                    uint16_t *c16 = e.codes16.data() + (size_t)i * wtot + woff;
+                    std::memcpy(c16, codes.data(), nw * 2);
+                    d.weights = c16;
+                }
+            }
+            woff += nw;
+            moff += (nw + 7) / 8;
+        }
+        e.models[(size_t)i].n_layers = L;
+        e.models[(size_t)i].layers = e.layers.data() + (size_t)i * (size_t)L;
+    }
+    return RINR_OK;
+}
+
+}  // namespace
+
+extern "C" int rinr_encode_blob_bound(const rinr_fit *f, int32_t hidden_bits, size_t *bytes) {
+    if (!f || !bytes) return RINR_E_NULL;
+    if (!(hidden_bits == 0 || (hidden_bits >= 2 && hidden_bits <= 8) || hidden_bits == 16)) return RINR_E_ARG;
+    try {
+        EncodeModels e;
+        e.params.assign((size_t)f->n_images * (size_t)f->n_params, 0.0f);
+        e.keep.assign((size_t)f->n_images * (size_t)f->n_params, 1);     // masks present, everything kept: the largest record
+        const int rc = describe(f, hidden_bits, e);
+        if (rc) return rc;
+        const rinr_store_opts so = {f->arch.w0, f->arch.coord_lo, f->arch.coord_hi};
+        return rinr_pack_size(e.models.data(), f->n_images, &so, bytes);
+    } catch (const std::bad_alloc &) {
+        return RINR_E_SIZE;
+    }
+}
+
+extern "C" int rinr_encode_images(rinr_fit *f, const float *targets, const rinr_encode_opts *o, float *psnr_out, void *blob,
+                                  size_t capacity, size_t *blob_bytes, void *stream) {
+    if (!f || !blob_bytes || (!targets && f->n_images > 0)) return RINR_E_NULL;
+    int rc = check_encode_opts(o);
+    if (rc) return rc;
+    try {
+        const int64_t n = f->n_images;
+        EncodeModels e;
+        e.params.resize((size_t)n * (size_t)f->n_params);
+        e.keep.assign((size_t)n * (size_t)f->n_params, 1);
+        std::vector<double> psnr, ratio((size_t)n);
+        bool have_keep = false;
+        // the fit itself (Eq. 1; cosine decay over the stage)
+        rinr_fit_opts fo = {o->lr, 0, o->fit_steps, 0.0f, 0.0f, 0.0f, 0.0f};
+        if ((rc = rinr_fit_set_keep(f, nullptr)) || (rc = rinr_fit_steps(f, targets, o->fit_steps, &fo, stream))) return rc;
+        // pruning rounds (Sec. IV-A): a fixed ratio first (large images only), then the ratio chosen from each image's PSNR;
+        // after each, the mask is applied and the model re-fitted from a fresh optimiser at the smaller rate
+        for (int round = 0; round < 2; ++round) {
+            if (round == 0 && !(o->first_ratio > 0.0f)) continue;
+            if (round == 0) {
+                std::fill(ratio.begin(), ratio.end(), (double)o->first_ratio);
+            } else {
+                if ((rc = psnr_now(f, targets, psnr, stream))) return rc;
+                for (int64_t i = 0; i < n; ++i) ratio[(size_t)i] = rinr_prune_ratio(o->schedule, psnr[(size_t)i]);
+            }
+            if ((rc = rinr_fit_get_params(f, e.params.data(), stream))) return rc;
+            if ((rc = prune_round(f, e.params, ratio, e.keep, have_keep))) return rc;
+            have_keep = true;
+            fo.lr = o->refit_lr;
+            fo.T = o->refit_steps;
+            if ((rc = rinr_fit_set_keep(f, e.keep.data())) || (rc = rinr_fit_reset_optimizer(f)) ||
+                (rc = rinr_fit_steps(f, targets, o->refit_steps, &fo, stream)))
+                return rc;
+        }
+        if ((rc = psnr_now(f, targets, psnr, stream))) return rc;
+        if (psnr_out)
+            for (int64_t i = 0; i < n; ++i) psnr_out[i] = (float)psnr[(size_t)i];
+        if ((rc = rinr_fit_get_params(f, e.params.data(), stream))) return rc;
+        // hidden layers to codes, first and last layer fp32 (Sec. IV-B); one blob for the decode side
+        if ((rc = describe(f, o->hidden_bits, e))) return rc;
+        const rinr_store_opts so = {f->arch.w0, f->arch.coord_lo, f->arch.coord_hi};
+        if ((rc = rinr_pack_size(e.models.data(), n, &so, blob_bytes))) return rc;
+        if (!blob || capacity < *blob_bytes) return RINR_E_SIZE;
+        return rinr_pack(e.models.data(), n, &so, blob, *blob_bytes);
+    } catch (const std::bad_alloc &) {
+        return RINR_E_SIZE;
+    }
+}

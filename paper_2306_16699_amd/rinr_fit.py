@@ -16,7 +16,8 @@ from .synth import Layer, Model
 MAX_LAYERS = 12
 EXPORTS = ["rinr_prune_ratio", "rinr_l1_mask", "rinr_quantize_layer", "rinr_fit_create", "rinr_fit_destroy",
            "rinr_fit_n_params", "rinr_fit_set_params", "rinr_fit_set_keep", "rinr_fit_reset_optimizer",
-           "rinr_fit_get_params", "rinr_fit_steps", "rinr_fit_loss_grad", "rinr_fit_last_loss", "rinr_psnr_batch"]
+           "rinr_fit_get_params", "rinr_fit_steps", "rinr_fit_loss_grad", "rinr_fit_last_loss", "rinr_psnr_batch", "rinr_encode_blob_bound",
+           "rinr_encode_images"]
 
 
 class FitArch(C.Structure):
@@ -27,6 +28,11 @@ class FitArch(C.Structure):
 class FitOpts(C.Structure):
     _fields_ = [("lr", C.c_float), ("t0", C.c_int32), ("T", C.c_int32), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("eps", C.c_float), ("loss_scale", C.c_float)]
+
+
+class EncodeOpts(C.Structure):
+    _fields_ = [("schedule", C.c_int32), ("first_ratio", C.c_float), ("fit_steps", C.c_int32), ("refit_steps", C.c_int32),
+                ("lr", C.c_float), ("refit_lr", C.c_float), ("hidden_bits", C.c_int32)]
 
 
 _ready = False
@@ -53,6 +59,8 @@ def lib():
         L.rinr_fit_loss_grad.argtypes = [vp, vp, C.c_float, vp, vp, vp]
         L.rinr_fit_last_loss.argtypes = [vp, vp, vp]
         L.rinr_psnr_batch.argtypes = [vp, vp, i64, i64, C.c_float, vp, vp]
+        L.rinr_encode_blob_bound.argtypes = [vp, i32, C.POINTER(C.c_size_t)]
+        L.rinr_encode_images.argtypes = [vp, vp, C.POINTER(EncodeOpts), vp, vp, C.c_size_t, C.POINTER(C.c_size_t), vp]
         _ready = True
     return L
 
@@ -165,6 +173,19 @@ class Fit:
                                              None if grad is None else grad.ctypes.data, rinr._stream_ptr(stream)),
                     "rinr_fit_loss_grad")
         return loss, grad
+
+    def encode(self, targets, schedule: int, first_ratio: float, fit_steps: int, refit_steps: int, lr: float, refit_lr: float,
+               hidden_bits: int = 8, stream=None):
+        """rinr_encode_images: returns (blob uint8 array, psnr float32[n_images])."""
+        bound = C.c_size_t()
+        rinr._check(lib().rinr_encode_blob_bound(self._h, hidden_bits, C.byref(bound)), "rinr_encode_blob_bound")
+        blob = np.empty(bound.value, dtype=np.uint8)
+        psnr = np.empty(self.n_images, dtype=np.float32)
+        o = EncodeOpts(schedule, first_ratio, fit_steps, refit_steps, lr, refit_lr, hidden_bits)
+        size = C.c_size_t()
+        rinr._check(lib().rinr_encode_images(self._h, self._targets(targets), C.byref(o), psnr.ctypes.data, blob.ctypes.data,
+                                             bound.value, C.byref(size), rinr._stream_ptr(stream)), "rinr_encode_images")
+        return blob[:size.value], psnr
 
     def last_loss(self, stream=None) -> np.ndarray:
         loss = np.empty(self.n_images, dtype=np.float32)

@@ -145,6 +145,76 @@ def test_fit_prune_quantise_pack_decode_round_trip():
     f.close()
 
 
+def test_encode_images_is_the_sequence_of_its_steps():
+    """rinr_encode_images (Sec. IV in one call) against the same procedure issued call by call through the
+    entry points the tests above check one by one: the two blobs are the same bytes."""
+    import ctypes as C
+    import torch
+    widths, H, W, n = [2, 24, 24, 24, 3], 24, 24, 6
+    tgt, tgt_d = targets_of(23, n, H, W)
+    p0 = synth.init_params(29, widths, n)
+    sched, first, fit_steps, refit_steps, lr, refit_lr = 0, 0.2, 500, 200, 2e-3, 1e-3
+    f = rinr_fit.Fit(widths, n, H, W)
+    f.set_params(p0)
+    blob, psnr = f.encode(tgt_d, sched, first, fit_steps, refit_steps, lr, refit_lr, hidden_bits=8)
+    final = f.get_params()
+    f.close()
+
+    g = rinr_fit.Fit(widths, n, H, W)
+    g.set_params(p0)
+    g.steps(tgt_d, fit_steps, lr, t0=0, T=fit_steps)
+    keep_mats = [None] * n
+    for rnd in range(2):
+        p = g.get_params()
+        if rnd == 1:
+            loss, _ = g.loss_grad(tgt_d, want_grad=False)
+        keeps = []
+        for i in range(n):
+            ratio = first if rnd == 0 else rinr_fit.prune_ratio(sched, -10.0 * np.log10(float(loss[i])))
+            prev = keep_mats[i]
+            keep_mats[i] = [rinr_fit.l1_mask(w, ratio, None if prev is None else prev[l]).reshape(w.shape)
+                            for l, (w, _) in enumerate(rinr_fit.split_params(widths, p[i]))]
+            keeps.append(rinr_fit.weight_keep_flags(widths, keep_mats[i]))
+        g.set_keep(np.stack(keeps))
+        g.reset_optimizer()
+        g.steps(tgt_d, refit_steps, refit_lr, t0=0, T=refit_steps)
+    loss, _ = g.loss_grad(tgt_d, want_grad=False)
+    p = g.get_params()
+    np.testing.assert_array_equal(p, final)
+    np.testing.assert_allclose(psnr, -10.0 * np.log10(loss), rtol=0, atol=1e-4)
+    models = [rinr_fit.to_model(widths, p[i], keep_mats[i], hidden_bits=8) for i in range(n)]
+    want = rinr.pack(models)
+    assert blob.size == want.size and np.array_equal(blob, want)
+    g.close()
+    # it is a store: opens, decodes to the quality the call reported (8-bit hidden layers cost little)
+    pruned = 1.0 - np.mean([np.concatenate([k.ravel() for k in keep_mats[i]]).mean() for i in range(n)])
+    assert pruned >= first - 0.01, pruned
+    st = rinr.Store(blob)
+    out = st.decode_batch(torch.arange(n, dtype=torch.int64, device="cuda"), H, W).cpu().numpy()
+    psnr_q = -10.0 * np.log10(((out - tgt) ** 2).reshape(n, -1).mean(axis=1))
+    assert np.all(psnr_q > psnr - 3.0), (psnr_q, psnr)
+    assert psnr.min() > 20.0, psnr
+    st.close()
+
+    # errors: a blob that does not fit reports the size needed; options out of range
+    h = rinr_fit.Fit(widths, 2, 8, 8)
+    h.set_params(p0[:2])
+    t2 = torch.from_numpy(np.ascontiguousarray(tgt[:2, :, :8, :8])).cuda()
+    L = rinr_fit.lib()
+    o = rinr_fit.EncodeOpts(0, 0.0, 3, 2, 1e-3, 1e-3, 8)
+    size = C.c_size_t()
+    small = np.empty(16, np.uint8)
+    assert L.rinr_encode_images(h._h, t2.data_ptr(), C.byref(o), None, small.ctypes.data, 16, C.byref(size), None) == rinr.E_SIZE
+    bound = C.c_size_t()
+    assert L.rinr_encode_blob_bound(h._h, 8, C.byref(bound)) == 0 and 16 < size.value <= bound.value
+    for bad in (rinr_fit.EncodeOpts(3, 0.0, 3, 2, 1e-3, 1e-3, 8), rinr_fit.EncodeOpts(0, 1.5, 3, 2, 1e-3, 1e-3, 8),
+                rinr_fit.EncodeOpts(0, 0.0, -1, 2, 1e-3, 1e-3, 8), rinr_fit.EncodeOpts(0, 0.0, 3, 2, 0.0, 1e-3, 8),
+                rinr_fit.EncodeOpts(0, 0.0, 3, 2, 1e-3, 1e-3, 9)):
+        assert L.rinr_encode_images(h._h, t2.data_ptr(), C.byref(bad), None, small.ctypes.data, 16, C.byref(size), None) == rinr.E_ARG
+    assert L.rinr_encode_images(None, t2.data_ptr(), C.byref(o), None, small.ctypes.data, 16, C.byref(size), None) == rinr.E_NULL
+    h.close()
+
+
 def test_fit_argument_errors_and_empty():
     import torch
     with pytest.raises(rinr.RinrError) as e:
