@@ -109,51 +109,87 @@ __device__ __forceinline__ uint32_t take_code(const uint32_t *cs, uint32_t rank,
     return (uint32_t)(two >> sh) & m;
 }
 
-// One wavefront rebuilds one layer.  `rec` is the model record (words, in LDS).  put(o, i, w, q)
-// receives every weight of the true n_out x n_in matrix exactly once: w the fp32 value (0.0f
-// where pruned) and q the integer code - zp of a coded layer (0 where pruned or for fp32
-// layers); putb(o, b) every bias.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) x += __shfl_xor(x, d, 64);
+    return x;
+}
+
+// The weights of a model are cut into blocks of 64 consecutive flat indices, layer after layer, and the workgroup's
+// wavefronts share the blocks of the whole model evenly: wavefront w of nw takes blocks [B w / nw, B (w + 1) / nw) of
+// the B blocks counted over all layers, so a wavefront touches one or two layers whatever the depth and the widths.
+struct ExpandShare {
+    uint32_t g0, g1;      // this wavefront's range of blocks, counted over all layers
+    uint32_t base;        // blocks of the layers before the one at hand (advanced by expand_layer)
+};
+__device__ __forceinline__ ExpandShare expand_share(const uint32_t *rec, int L, int wave, int nwaves) {
+    uint32_t total = 0;
+    for (int l = 0; l < L; ++l) {
+        const LayerRec *r = (const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
+        total += ((uint32_t)r->n_in * r->n_out + 63) >> 6;
+    }
+    ExpandShare s;
+    s.g0 = total * (uint32_t)wave / (uint32_t)nwaves;
+    s.g1 = total * (uint32_t)(wave + 1) / (uint32_t)nwaves;
+    s.base = 0;
+    return s;
+}
+
+// This wavefront's part of one layer, one weight per lane.  `rec` is the model record (words, in LDS).  Over the
+// workgroup, put(o, i, w, q) receives every weight of the true n_out x n_in matrix exactly once: w the fp32 value
+// (0.0f where pruned) and q the integer code - zp of a coded layer (0 where pruned or for fp32 layers); putb(o, b)
+// every bias (from the wavefront that holds the layer's first block).  A kept weight's code is found by its rank
+// among the kept ones: the count before the wavefront's first block by one reduction over the mask words, then a
+// running count.
 template <class PutW, class PutB>
-__device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec &r, int lane, PutW put, PutB putb) {
+__device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec &r, int lane, ExpandShare &sh, PutW put, PutB putb) {
     const uint32_t n_in = r.n_in, cnt = (uint32_t)r.n_in * r.n_out;
-    const uint32_t nwords = (cnt + 31) >> 5;
+    const uint32_t nwords = (cnt + 31) >> 5, nblocks = (cnt + 63) >> 6;
+    const uint32_t first = sh.base, last = sh.base + nblocks;
+    sh.base = last;
+    if (sh.g1 <= first || sh.g0 >= last) return;
+    const uint32_t b0 = sh.g0 > first ? sh.g0 - first : 0u, b1 = (sh.g1 < last ? sh.g1 : last) - first;
     const uint32_t *mw = rec + (r.mask_off >> 2);
     const uint32_t *cs = rec + (r.code_off >> 2);
     const uint32_t cb = r.bits ? r.bits : 32u;
+    const uint32_t magic = n_in > 1 ? 0xFFFFFFFFu / n_in + 1u : 0u;     // ceil(2^32 / n_in): k / n_in == umulhi(k, magic) for k < 2^16
+    auto mask_word = [&](uint32_t wi) -> uint32_t {
+        if (wi >= nwords) return 0u;
+        if (r.has_mask) return mw[wi];
+        return (wi == nwords - 1 && (cnt & 31)) ? (1u << (cnt & 31)) - 1u : 0xFFFFFFFFu;
+    };
     uint32_t running = 0;
-    for (uint32_t w0 = 0; w0 < nwords; w0 += 64) {
-        const uint32_t wi = w0 + lane;
-        uint32_t m = 0;
-        if (wi < nwords) {
-            m = r.has_mask ? mw[wi] : 0xFFFFFFFFu;
-            if (!r.has_mask && wi == nwords - 1 && (cnt & 31)) m = (1u << (cnt & 31)) - 1u;
-        }
-        const uint32_t pc = __popc(m);
-        const uint32_t incl = wave_incl_scan(pc, lane);
-        uint32_t rank = incl - pc + running;
-        running += __shfl(incl, 63, 64);
-        if (wi < nwords) {
-            uint32_t k = wi << 5;
-            uint32_t o = k / n_in, i = k - o * n_in;
-            const uint32_t kend = (k + 32 < cnt) ? k + 32 : cnt;
-            for (; k < kend; ++k, m >>= 1) {
-                float val = 0.0f;
-                int32_t q = 0;
-                if (m & 1u) {
-                    const uint32_t code = take_code(cs, rank++, cb);
-                    if (r.bits) { q = (int32_t)code - r.zp; val = r.scale * (float)q; }
-                    else val = __uint_as_float(code);
-                }
-                put((int)o, (int)i, val, q);
-                if (++i == n_in) { i = 0; ++o; }
-            }
-        }
+    if (b0) {
+        uint32_t part = 0;
+        for (uint32_t wi = lane; wi < 2 * b0; wi += 64) part += __popc(mask_word(wi));
+        running = wave_sum(part);
     }
-    const float *bias = (const float *)(rec + (r.bias_off >> 2));
-    for (uint32_t o = lane; o < r.n_out; o += 64) putb((int)o, bias[o]);
+    for (uint32_t b = b0; b < b1; ++b) {
+        const uint32_t k = (b << 6) + (uint32_t)lane, bit = (uint32_t)lane & 31u;
+        const uint32_t m = mask_word(k >> 5);
+        const uint32_t pc = __popc(m);
+        const uint32_t pc_lo = __shfl(pc, 0, 64), pc_hi = __shfl(pc, 32, 64);
+        if (k < cnt) {
+            const uint32_t o = n_in == 1 ? k : __umulhi(k, magic), i = k - o * n_in;
+            float val = 0.0f;
+            int32_t q = 0;
+            if ((m >> bit) & 1u) {
+                const uint32_t rank = running + (lane >= 32 ? pc_lo : 0u) + __popc(m & ((1u << bit) - 1u));
+                const uint32_t code = take_code(cs, rank, cb);
+                if (r.bits) { q = (int32_t)code - r.zp; val = r.scale * (float)q; }
+                else val = __uint_as_float(code);
+            }
+            put((int)o, (int)i, val, q);
+        }
+        running += pc_lo + pc_hi;
+    }
+    if (b0 == 0) {
+        const float *bias = (const float *)(rec + (r.bias_off >> 2));
+        for (uint32_t o = (uint32_t)lane; o < r.n_out; o += 64u) putb((int)o, bias[o]);
+    }
 }
 
-// Whole model: zero the expanded area, then one wavefront per layer.  `pre` scales the
+// Whole model: zero the expanded area, then every wavefront its share of the blocks.  `pre` scales the
 // weights and biases of the sine layers (w0 / 2pi, so that the pre-activation is in
 // revolutions); the output layer is never scaled.  Ends with a workgroup barrier.
 template <int TM, int WP>
@@ -162,20 +198,21 @@ __device__ __forceinline__ void expand_model(float *lds, const uint32_t *rec, in
     const int total = LY::total(L);
     for (int q = tid; q < total; q += nthreads) lds[q] = 0.0f;
     __syncthreads();
-    const int wave = tid >> 6, lane = tid & 63, nwaves = nthreads >> 6;
-    for (int l = wave; l < L; l += nwaves) {
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, nwaves = nthreads >> 6;
+    ExpandShare sh = expand_share(rec, L, wave, nwaves);
+    for (int l = 0; l < L; ++l) {
         const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
         if (l == L - 1) {
             float *w = lds + LY::off_out(L), *b = lds + LY::off_outb(L);
-            expand_layer(rec, r, lane, [=](int o, int i, float v, int) { w[LY::idx_out(o, i)] = v; },
+            expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { w[LY::idx_out(o, i)] = v; },
                          [=](int o, float v) { b[o] = v; });
         } else if (l == 0) {
             float *w = lds + LY::off_first(), *b = lds + LY::off_bias(0);
-            expand_layer(rec, r, lane, [=](int o, int i, float v, int) { w[LY::idx_first(o, i)] = v * pre; },
+            expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { w[LY::idx_first(o, i)] = v * pre; },
                          [=](int o, float v) { b[LY::idx_bias(o)] = v * pre; });
         } else {
             float *w = lds + LY::off_hidden(L, l), *b = lds + LY::off_bias(l);
-            expand_layer(rec, r, lane, [=](int o, int i, float v, int) { w[LY::idx_hidden(o, i)] = v * pre; },
+            expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { w[LY::idx_hidden(o, i)] = v * pre; },
                          [=](int o, float v) { b[LY::idx_bias(o)] = v * pre; });
         }
     }

@@ -134,14 +134,15 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
         }
     }
     __syncthreads();
-    const int wave = tid >> 6, lane = tid & 63, nwaves = nthreads >> 6;
-    for (int l = wave; l < L; l += nwaves) {
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, nwaves = nthreads >> 6;
+    ExpandShare sh = expand_share(rec, L, wave, nwaves);
+    for (int l = 0; l < L; ++l) {
         const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
         const XLayer e = tab[l];
         _Float16 *hi = (_Float16 *)(lds + e.off_hi), *lo = (_Float16 *)(lds + e.off_lo);
         float *bt = (float *)(lds + e.off_bias);
         if (l == L - 1) {
-            expand_layer(rec, r, lane,
+            expand_layer(rec, r, lane, sh,
                          [=](int o, int i, float v, int) {
                              const _Float16 h = (_Float16)v;
                              hi[LY::idx_out(o, i)] = h;
@@ -149,7 +150,7 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
                          },
                          [=](int o, float v) { bt[LY::idx_bias(4 * o)] = v; });
         } else if (l == 0) {
-            expand_layer(rec, r, lane,
+            expand_layer(rec, r, lane, sh,
                          [=](int o, int i, float v, int) {
                              const float w = v * pre;
                              const _Float16 h = (_Float16)w, lw = (_Float16)(w - (float)h);
@@ -162,10 +163,10 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
                          [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre; });
         } else if (e.off_lo == 0) {
             const float inv = 1.0f / e.scale;
-            expand_layer(rec, r, lane, [=](int o, int i, float, int q) { hi[LY::idx_hidden(o, i)] = (_Float16)(float)q; },
+            expand_layer(rec, r, lane, sh, [=](int o, int i, float, int q) { hi[LY::idx_hidden(o, i)] = (_Float16)(float)q; },
                          [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre * inv; });
         } else {
-            expand_layer(rec, r, lane,
+            expand_layer(rec, r, lane, sh,
                          [=](int o, int i, float v, int) {
                              const float w = v * pre;
                              const _Float16 h = (_Float16)w;
