@@ -153,7 +153,15 @@ typedef struct {
                                 Mapped coordinates must stay below 6e4 in magnitude.       */
     float norm_scale[3];     /* used with RINR_FLAG_NORMALIZE, e.g. 1/std per channel      */
     float norm_shift[3];     /* used with RINR_FLAG_NORMALIZE, e.g. -mean/std per channel  */
+    void *workspace;         /* device, 4-byte aligned, or NULL.  Scratch for one call: with it, a batch from
+                                a store that mixes model widths or depths is decoded heaviest model first (one
+                                more small kernel orders the slots), which shortens the tail of the grid;
+                                results are the same bytes.  Calls that may overlap need their own.    */
+    size_t workspace_bytes;  /* >= rinr_decode_workspace_bytes(n), else RINR_E_SIZE                    */
 } rinr_decode_opts;
+
+/* Bytes of rinr_decode_opts.workspace a batch of n slots needs (4 per slot). */
+size_t rinr_decode_workspace_bytes(int32_t n);
 
 /* Decodes slots s = 0..n-1 (Sec. III-B: batch select + pixel- and image-parallel
  * decode): slot s shows model image_ids[s] sampled on an H x W pixel-centre grid,
@@ -172,7 +180,7 @@ typedef struct {
  * kernels also need |w * w0/2pi| and the coordinate bounds below 6e4 (fp16 range); a store
  * that breaks this is served by the fp32 MFMA kernels automatically.
  * A store keeps the launch plan of its last decode: use one store from one host thread at a time.
- * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL, NULL}. */
+ * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL, NULL} and no workspace. */
 int rinr_decode_batch(const rinr_store *models, const int64_t *image_ids, int32_t n,
                       int32_t H, int32_t W, void *out, void *stream);
 int rinr_decode_batch_ex(const rinr_store *models, const int64_t *image_ids, int32_t n,

@@ -133,6 +133,7 @@ struct rinr_store {
     double class_tile_us_xdl[kMaxClass + 1];
     bool xdl_ok;                              // every weight fits fp16 range after pre-scaling, and the models fit LDS
     int hidden_kind;                          // kHiddenAllInt / AllRaw / Mixed over all hidden layers of all models
+    bool even_cost;                           // every model has the same width class and depth: slot order does not matter
     bool fp32_ok;                             // the fp32 kernels' expanded models fit LDS
     uint32_t xdl_stage_off[kMaxClass + 1];    // floats
     uint32_t xdl_lds_bytes[kMaxClass + 1];
@@ -180,10 +181,13 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
                     (size_t)sum.header.n_models * sizeof(IndexEntry));
     std::memset(s->last_info, 0, sizeof s->last_info);
     s->plan_hw = -1; s->plan_n = -1; s->plan_threads = -1; s->plan_knob = -1;
+    s->even_cost = true;
     {   // mean matrix work per pixel of each class -> time of a 64-pixel tile on one SIMD's MFMA pipe
         double macs[kMaxClass + 1] = {0, 0, 0, 0, 0};
         for (const IndexEntry &e : s->index) {
             const uint32_t c = e.width == 0 ? 1u : (e.width + 15u) >> 4;
+            const IndexEntry &f = s->index[0];
+            if (e.n_layers != f.n_layers || c != (f.width == 0 ? 1u : (f.width + 15u) >> 4)) s->even_cost = false;
             const double wp = 16.0 * c;
             macs[c] += wp * (4.0 + (e.n_layers - 2) * wp);
         }
@@ -301,6 +305,16 @@ extern "C" int rinr_store_info(const rinr_store *s, int64_t *n_models, int32_t *
     return RINR_OK;
 }
 
+namespace {
+hipError_t order_slots(const rinr_store *s, const int64_t *image_ids, int32_t n, void *workspace, void *stream) {
+    hipLaunchKernelGGL(order_slots_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, s->blob, (uint64_t)s->sum.header.n_models,
+                       image_ids, (uint32_t)n, (uint32_t *)workspace);
+    return hipGetLastError();
+}
+}  // namespace
+
+extern "C" size_t rinr_decode_workspace_bytes(int32_t n) { return n > 0 ? ((size_t)n * 4 + 15) & ~(size_t)15 : 0; }
+
 extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_ids, int32_t n, int32_t H, int32_t W,
                                     void *out, const rinr_decode_opts *opts, void *stream) {
     if (!s || !opts) return RINR_E_NULL;
@@ -322,6 +336,8 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (dt != RINR_OUT_U8 && ((uintptr_t)out & 3)) return RINR_E_ALIGN;
     if ((uintptr_t)image_ids & 7) return RINR_E_ALIGN;
     if ((uintptr_t)opts->affine & 3) return RINR_E_ALIGN;
+    if ((uintptr_t)opts->workspace & 3) return RINR_E_ALIGN;
+    if (opts->workspace && opts->workspace_bytes < rinr_decode_workspace_bytes(n)) return RINR_E_SIZE;
 
     const StoreHeader &h = s->sum.header;
     DecodeArgs a;
@@ -369,6 +385,9 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     int n_classes = 0;
     for (uint32_t c = 1; c <= kMaxClass; ++c) n_classes += s->sum.class_count[c] ? 1 : 0;
 
+    // slots of unequal cost are taken heaviest first when the caller gives the scratch for the order
+    const bool order = opts->workspace && !s->even_cost;
+    if (order) a.order = (const uint32_t *)opts->workspace;
     int launches = 0;
     uint32_t big_lds = 0, total_blocks = 0;
     if (n_classes != 1) {
@@ -397,10 +416,11 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
         a.tiles_per_chunk = pl.tiles_per_chunk;
         a.cls = 0;
         a.handle_bad = 1u;
+        if (order) RINR_HIP(order_slots(s, image_ids, n, opts->workspace, stream));
         void *kargs[] = {(void *)&a};
         RINR_HIP(hipLaunchKernel(fn, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), kargs, lds_bytes,
                                  (hipStream_t)stream));
-        launches = 1;
+        launches = order ? 2 : 1;
         total_blocks = (uint32_t)n * pl.chunks;
         big_lds = lds_bytes;
     } else {
@@ -421,10 +441,11 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
             a.tiles_per_chunk = pl.tiles_per_chunk;
             a.cls = c;
             a.handle_bad = 1u;
+            if (order) RINR_HIP(order_slots(s, image_ids, n, opts->workspace, stream));
             hipLaunchKernelGGL(xdl ? im.decode_xdl[xk] : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
                                (hipStream_t)stream, a);
             RINR_HIP(hipGetLastError());
-            launches = 1;
+            launches = order ? 2 : 1;
             total_blocks = (uint32_t)n * pl.chunks;
             big_lds = lds_bytes;
         }

@@ -242,6 +242,7 @@ struct DecodeArgs {
     const float *affine;          // per-slot 2x3 map of the sampling grid, or NULL
     float ns[3], nb[3];           // per-channel scale / shift applied after the clamp when normalize != 0
     uint32_t normalize;
+    const uint32_t *order;        // workgroups take the slots in this order (heaviest model first), or NULL = 0, 1, 2, ...
 };
 
 // sin(2 pi r): the hardware sine takes its argument in revolutions and reduces the range
@@ -260,14 +261,48 @@ struct Work {
     uint32_t cls;                // width class of the model
 };
 
+// ---- slots ordered by the cost of their models, heaviest first: workgroups are started in grid order, so the long
+// ones then start early and the grid's tail is made of short ones.  One workgroup: histogram of a cost key
+// (layers x a per-width-class weight) in LDS, prefix from the heaviest key down, scatter.  The order inside a key
+// is whatever the atomics give: it does not matter, every slot is decoded by the same code wherever it runs.
+constexpr int kOrderKeys = 256;
+__device__ __forceinline__ uint32_t order_key(const uint8_t *blob, uint64_t n_models, int64_t id) {
+    if (id < 0 || (uint64_t)id >= n_models) return 0u;                       // zero-filled: the cheapest
+    const IndexEntry e = *(const IndexEntry *)(blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
+    const uint32_t cls = e.width == 0 ? 1u : (e.width + 15u) >> 4;
+    const uint32_t per_layer = cls == 1 ? 3u : (cls == 2 ? 6u : (cls == 3 ? 10u : 13u));     // measured cost of a sine layer per width class
+    const uint32_t key = per_layer * e.n_layers;
+    return key < (uint32_t)kOrderKeys ? key : (uint32_t)kOrderKeys - 1u;
+}
+__global__ __launch_bounds__(1024) void order_slots_kernel(const uint8_t *blob, uint64_t n_models, const int64_t *ids, uint32_t n,
+                                                           uint32_t *order) {
+    __shared__ uint32_t cursor[kOrderKeys];
+    const uint32_t tid = threadIdx.x;
+    if (tid < (uint32_t)kOrderKeys) cursor[tid] = 0u;
+    __syncthreads();
+    for (uint32_t s = tid; s < n; s += 1024u) atomicAdd(&cursor[order_key(blob, n_models, ids[s])], 1u);
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t at = 0;
+        for (int k = kOrderKeys - 1; k >= 0; --k) {
+            const uint32_t c = cursor[k];
+            cursor[k] = at;
+            at += c;
+        }
+    }
+    __syncthreads();
+    for (uint32_t s = tid; s < n; s += 1024u) order[atomicAdd(&cursor[order_key(blob, n_models, ids[s])], 1u)] = s;
+}
+
 // ---- gather: workgroup -> (slot, tile range); slot -> id -> index entry (Sec. III-B batch select).
 // Returns false when the workgroup has nothing to decode: empty tile range, or an out-of-range id
 // (then the launch that handles bad ids has zero-filled the range and counted it), or a model of
 // another class than this launch serves.
 __device__ __forceinline__ bool decode_prologue(const DecodeArgs &a, Work &w) {
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    w.slot = blockIdx.x / a.chunks;
-    const uint32_t chunk = blockIdx.x - w.slot * a.chunks;
+    const uint32_t turn = blockIdx.x / a.chunks;
+    const uint32_t chunk = blockIdx.x - turn * a.chunks;
+    w.slot = a.order ? a.order[turn] : turn;
     w.tile0 = chunk * a.tiles_per_chunk;
     const uint32_t ntiles_img = (a.HW + 63) >> 6;
     if (w.tile0 >= ntiles_img) return false;

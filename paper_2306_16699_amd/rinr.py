@@ -26,7 +26,7 @@ E_NULL, E_ARG, E_MODEL, E_SIZE, E_FORMAT, E_UNSUPPORTED, E_ALIGN, E_HIP = -1, -2
 EXPORTS = ["rinr_pack_size", "rinr_pack", "rinr_unpack_layer", "rinr_store_open", "rinr_store_close",
            "rinr_store_info", "rinr_decode_batch", "rinr_decode_batch_ex", "rinr_store_status",
            "rinr_debug_dequant", "rinr_last_launch_info", "rinr_tune", "rinr_strerror",
-           "rinr_last_hip_error", "rinr_version"]
+           "rinr_last_hip_error", "rinr_version", "rinr_decode_workspace_bytes"]
 
 
 class LayerDesc(C.Structure):
@@ -44,7 +44,8 @@ class StoreOpts(C.Structure):
 
 class DecodeOpts(C.Structure):
     _fields_ = [("out_dtype", C.c_int32), ("flags", C.c_int32), ("out_u8", C.c_void_p), ("affine", C.c_void_p),
-                ("norm_scale", C.c_float * 3), ("norm_shift", C.c_float * 3)]
+                ("norm_scale", C.c_float * 3), ("norm_shift", C.c_float * 3), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t)]
 
 
 class RinrError(RuntimeError):
@@ -93,6 +94,13 @@ def strerror(code: int) -> str:
 def _check(rc: int, what: str):
     if rc != OK:
         raise RinrError(rc, what)
+
+
+def workspace_bytes(n: int) -> int:
+    L = lib()
+    L.rinr_decode_workspace_bytes.restype = C.c_size_t
+    L.rinr_decode_workspace_bytes.argtypes = [C.c_int32]
+    return int(L.rinr_decode_workspace_bytes(n))
 
 
 def pack_mask(keep: np.ndarray) -> np.ndarray:
@@ -221,8 +229,10 @@ class Store:
         return out
 
     def decode_batch_ex(self, image_ids, H: int, W: int, out_dtype: int = OUT_F32, flags: int = 0,
-                        out=None, out_u8=None, stream=None, affine=None, norm=None):
+                        out=None, out_u8=None, stream=None, affine=None, norm=None, workspace=None):
         """rinr_decode_batch_ex.  Returns out (and out_u8 for OUT_F32_AND_U8).
+
+        workspace: uint8 CUDA tensor of >= workspace_bytes(n) bytes (heaviest-first order for ragged stores) or None;
 
         affine: float32 CUDA tensor [n, 6] (per-slot map of the sampling grid) or None;
         norm: (scale[3], shift[3]) host numbers, sets FLAG_NORMALIZE."""
@@ -237,6 +247,9 @@ class Store:
         if affine is not None:
             assert affine.dtype == torch.float32 and affine.is_contiguous() and tuple(affine.shape) == (n, 6)
             o.affine = affine.data_ptr() if n else None
+        if workspace is not None and n:
+            assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.is_contiguous()
+            o.workspace, o.workspace_bytes = workspace.data_ptr(), workspace.numel()
         if norm is not None:
             o.flags |= FLAG_NORMALIZE
             o.norm_scale = (C.c_float * 3)(*[float(v) for v in norm[0]])

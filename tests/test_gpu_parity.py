@@ -333,5 +333,60 @@ def test_decode_argument_errors(torch):
     st.close()
 
 
+def test_heaviest_first_order_changes_nothing(torch):
+    """With a workspace the slots of a ragged batch are taken heaviest model first: same bytes out, in every mode,
+    with repeats and out-of-range ids in the batch; a store of one width ignores the workspace."""
+    w = synth.workload(5, n_images=300, pool=500, H=24, W=37)
+    st = rinr.Store(rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi))
+    ids_h = w.image_ids.copy()
+    ids_h[[3, 77, 299]] = [-1, 500, 2 ** 40]
+    ids = torch.from_numpy(ids_h).cuda()
+    ws = torch.empty(rinr.workspace_bytes(300), dtype=torch.uint8, device="cuda")
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT):
+        a = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode)
+        b = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode, workspace=ws)
+        assert torch.equal(a, b), mode
+        order = ws[:1200].view(torch.int32).cpu().numpy()
+        assert np.array_equal(np.sort(order), np.arange(300))              # a permutation of the slots ...
+        cost = np.array([0 if not (0 <= i < 500) else (len(w.models[int(i)].layers)) *
+                         {1: 3, 2: 6, 3: 10, 4: 13}[(max(ly.n_out for ly in w.models[int(i)].layers[:-1]) + 15) // 16] for i in ids_h])
+        assert np.all(np.diff(cost[order]) <= 0)                            # ... by falling cost
+        f32, u8 = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32_AND_U8, mode & ~rinr.FLAG_FP16_ACT, workspace=ws)
+        assert torch.equal(f32, st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode & ~rinr.FLAG_FP16_ACT))
+    assert st.status() == 3 * 4 * 3                 # three bad ids in each of the four decodes per mode
+    # too small a workspace, a misaligned one
+    L = rinr.lib()
+    out = torch.empty((300, 3, 24, 37), device="cuda")
+    o = rinr.DecodeOpts(rinr.OUT_F32, 0, None)
+    o.workspace, o.workspace_bytes = ws.data_ptr(), 300 * 4 - 1
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 300, 24, 37, out.data_ptr(), C.byref(o), None) == rinr.E_SIZE
+    o.workspace, o.workspace_bytes = ws.data_ptr() + 2, 300 * 4
+    assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 300, 24, 37, out.data_ptr(), C.byref(o), None) == rinr.E_ALIGN
+    st.close()
+    # one width, several depths: ordered too
+    rng = np.random.default_rng(5)
+    deep = []
+    for k in range(40):
+        dims = [2] + [32] * int(rng.integers(1, 6)) + [3]
+        deep.append(Model([Layer(dims[l], dims[l + 1], 0, 0.0, 0, (rng.uniform(-1, 1, (dims[l + 1], dims[l])) * (0.5 if l == 0 else 0.03)).astype(np.float32),
+                                 None, rng.uniform(-.1, .1, dims[l + 1]).astype(np.float32)) for l in range(len(dims) - 1)]))
+    st3 = rinr.Store(rinr.pack(deep))
+    ids3 = torch.from_numpy(rng.integers(0, 40, 100)).cuda()
+    plain = st3.decode_batch_ex(ids3, 20, 20)
+    assert st3.last_launch_info()["launches"] == 1
+    assert torch.equal(st3.decode_batch_ex(ids3, 20, 20, workspace=ws), plain)
+    assert st3.last_launch_info()["launches"] == 2
+    depth = np.array([len(deep[int(i)].layers) for i in ids3.cpu().numpy()])
+    assert np.all(np.diff(depth[ws[:400].view(torch.int32).cpu().numpy()]) <= 0)
+    st3.close()
+    w2 = synth.workload(2, n_images=20, H=16, W=16)
+    st2 = rinr.Store(rinr.pack(w2.models))
+    ids2 = torch.from_numpy(w2.image_ids).cuda()
+    ws.fill_(255)
+    assert torch.equal(st2.decode_batch_ex(ids2, 16, 16, workspace=ws), st2.decode_batch_ex(ids2, 16, 16))
+    assert int(ws.min()) == 255                                              # untouched
+    st2.close()
+
+
 def test_zz_report_worst_errors():
     print("largest unclamped max-abs error per mode:", {("default" if m == 0 else "fp32 MFMA" if m == rinr.FLAG_FP32_MFMA else "fp16 activations"): f"{e:.2e}" for m, e in WORST.items()})
