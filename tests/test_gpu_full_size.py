@@ -29,12 +29,13 @@ def test_full_size_workload(k, n_sample, mode):
     w, blob = packed_workload(k)
     st = rinr.Store(blob)
     ids = torch.from_numpy(w.image_ids).cuda()
+    ws = torch.empty(rinr.workspace_bytes(w.n), dtype=torch.uint8, device="cuda")     # as bench.py: heaviest-first order where sizes differ
     if w.out_u8:
-        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8, mode)
+        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32_AND_U8, mode, workspace=ws)
         u8 = u8.cpu().numpy()
     else:
-        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode), None
-    raw = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy()
+        f32, u8 = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode, workspace=ws), None
+    raw = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP, workspace=ws).cpu().numpy()
     f32 = f32.cpu().numpy()
     assert st.status() == 0
     info = st.last_launch_info()
