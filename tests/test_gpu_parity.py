@@ -298,6 +298,19 @@ def test_store_open_validates_on_device_copy(torch):
         st.decode_batch_ex(ids, 9, 11, rinr.OUT_F32, rinr.FLAG_FP32_MFMA)
     assert e.value.code == rinr.E_UNSUPPORTED
     st.close()
+    # the format's limits at once (RINR_MAX_LAYERS = 16 linear layers, RINR_MAX_WIDTH = 64): the expanded operands
+    # and the packed record share the 160 KB of LDS, so such a store opens only if its records are sparse
+    with pytest.raises(rinr.RinrError) as e:
+        rinr.Store(rinr.pack(synth.make_models(4, np.arange(2), 64, 15, [0] + [8] * 14 + [0], 0.9)))
+    assert e.value.code == rinr.E_UNSUPPORTED
+    most = synth.make_models(4, np.arange(2), 64, 15, [0] + [8] * 14 + [0], 0.1)
+    st = rinr.Store(rinr.pack(most))
+    assert st.info() == (2, 64, 16)
+    ref = oracle.decode(most, [0, 1], 13, 10, clamp=False)
+    for mode in (0, rinr.FLAG_FP16_ACT):
+        got = st.decode_batch_ex(ids_dev(torch, [0, 1]), 13, 10, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy()
+        assert np.abs(got - ref).max() <= TOL, mode
+    st.close()
     # raw fp32 hidden layers at that depth fit neither form: refused at open
     deeper = synth.make_models(3, np.arange(1), 64, 12, [0] * 13, 0.5)
     with pytest.raises(rinr.RinrError) as e:
