@@ -104,7 +104,7 @@ struct FitArgs {
     float *grad_out;              // null: Adam update; else the gradient is written here and nothing is updated
     int64_t n_params;
     uint32_t HW, W;
-    float inv2W, inv2H, lo, span, w0, w0rev;
+    float inv2W, inv2H, lo, span, w0rev;        // w0rev = w0 / 2pi
     float loss_scale;
     float lr, c1inv, c2inv, b1, b2, eps;
     int32_t L;
@@ -399,7 +399,7 @@ struct rinr_fit {
     rinr_fit_arch arch;
     int64_t n_images, n_params;
     int32_t H, W;
-    int PC, wq, lds_floats;     // wq: widest hidden layer rounded up to a multiple of 8
+    int wq, lds_floats;         // wq: widest hidden layer rounded up to a multiple of 8
     int32_t p_off[kMaxL];
     float *params, *m, *v, *loss, *scratch_grad;
     uint8_t *keep;            // null until set
@@ -424,13 +424,11 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
     f->n_images = n_images;
     f->H = H;
     f->W = W;
-    f->PC = 0;
     int wmax = 1;
     for (int l = 1; l < arch->n_layers; ++l) wmax = arch->widths[l] > wmax ? arch->widths[l] : wmax;
     f->wq = (wmax + 7) / 8 * 8;
     f->lds_floats = lds_floats(f->wq, arch->n_layers);
     if (f->lds_floats == 0 || (size_t)f->lds_floats * 4 + 256 > kLdsLimit) { delete f; return RINR_E_UNSUPPORTED; }
-    f->PC = 64;
     f->n_params = 0;
     for (int l = 0; l < arch->n_layers; ++l) {
         f->p_off[l] = (int32_t)f->n_params;
@@ -546,7 +544,6 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.inv2H = 1.0f / (2.0f * (float)f->H);
     a.lo = f->arch.coord_lo;
     a.span = f->arch.coord_hi - f->arch.coord_lo;
-    a.w0 = f->arch.w0;
     a.w0rev = (float)((double)f->arch.w0 / (2.0 * 3.14159265358979323846));
     a.loss_scale = loss_scale;
     {
