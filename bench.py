@@ -27,14 +27,15 @@ PEAK_FP16_MFMA_TFLOPS = 2500.0    # MI355X dense fp16 matrix peak
 PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3 T lane-operations/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
 
 
-def alu_ops_per_pixel(model, act16: bool = False) -> float:
+def alu_ops_per_pixel(model, act16: bool = False, all16: bool = False) -> float:
     """Vector-ALU operations the split-precision path needs per pixel (algorithmic, one per lane):
     per sine-layer output: sine, hi conversion (1/2), residual, lo conversion (1/2) = 3, plus the
     dequantisation scale where the layer is stored as 2..8-bit codes (it multiplies the accumulator).
-    With a single fp16 value per activation (act16) the residual and its conversion go: sine + 1/2."""
+    With a single fp16 value per activation (act16) the residual and its conversion go: sine + 1/2.
+    With fp16 weights as well (all16) the scale is folded into them: sine + 1/2 for every layer."""
     n = 0.0
     for l, ly in enumerate(model.layers[:-1]):
-        n += ly.n_out * ((1.5 if act16 else 3) + (1 if (l > 0 and 2 <= ly.bits <= 8) else 0))
+        n += ly.n_out * ((1.5 if (act16 or all16) else 3) + (1 if (l > 0 and 2 <= ly.bits <= 8 and not all16) else 0))
     return n
 
 
@@ -122,6 +123,8 @@ def main() -> int:
     ap.add_argument("--fp32-mfma", action="store_true", help="time the fp32 MFMA kernels instead of the default split-precision path")
     ap.add_argument("--fp16-act", action="store_true",
                     help="time the opt-in mode that keeps one fp16 value per hidden activation (RINR_FLAG_FP16_ACT)")
+    ap.add_argument("--fp16-all", action="store_true",
+                    help="time the opt-in mode with fp16 weights and activations in the hidden layers (RINR_FLAG_FP16_ALL)")
     ap.add_argument("--augment", action="store_true",
                     help="time the decode with a per-slot affine map of the sampling grid and per-channel "
                          "normalisation fused in (fp32 output only)")
@@ -213,6 +216,7 @@ def main() -> int:
     alu_px = np.array([alu_ops_per_pixel(w.models[int(i)]) for i in w.image_ids], dtype=np.float64)
     alu_ops = float(alu_px.sum()) * H * W
     alu_ops16 = float(sum(alu_ops_per_pixel(w.models[int(i)], True) for i in w.image_ids)) * H * W
+    alu_ops16a = float(sum(alu_ops_per_pixel(w.models[int(i)], True, True) for i in w.image_ids)) * H * W
 
     def traffic_of(tag):
         tpath = os.path.join(ROOT, "profiles", f"decode_{tag}_cfg{args.config}_traffic.json")
@@ -236,14 +240,18 @@ def main() -> int:
                 "alu_ops_per_launch": ops, "kernel": kernel,
                 "matrix_algorithmic_tflops": flops / (kern_ms * 1e-3) / 1e12, "matrix_fp16_peak_tflops": PEAK_FP16_MFMA_TFLOPS}
 
-    alt, alt16 = None, None
+    alt, alt16, alt16a = None, None, None
     k16 = "decode_xdl_kernel, one fp16 value per activation (fp16 MFMA, fp32 accumulate)"
+    k16a = "decode_xdl_kernel, fp16 weights and activations in the hidden layers (fp16 MFMA, fp32 accumulate)"
     if args.fp32_mfma:
         wall_ms, kern_ms, info = timed(rinr.FLAG_FP32_MFMA)
         roof, dtype_name = mfma_roofline(kern_ms, "fp32mfma"), "f32"
     elif args.fp16_act:
         wall_ms, kern_ms, info = timed(rinr.FLAG_FP16_ACT)
         roof, dtype_name = alu_roofline(kern_ms, alu_ops16, "xdl16", k16), "f16 activations, f32 accumulate"
+    elif args.fp16_all:
+        wall_ms, kern_ms, info = timed(rinr.FLAG_FP16_ALL)
+        roof, dtype_name = alu_roofline(kern_ms, alu_ops16a, "xdl16all", k16a), "f16 weights and activations, f32 accumulate"
     else:
         wall_ms, kern_ms, info = timed(0)
         roof = alu_roofline(kern_ms, alu_ops, "xdl", "decode_xdl_kernel (fp16 hi+lo operands on MFMA, fp32 accumulate)")
@@ -255,6 +263,10 @@ def main() -> int:
         alt16 = {"mode": "RINR_FLAG_FP16_ACT (opt-in, reduced precision: one fp16 value per hidden activation)",
                  "value": pixels / (w3 * 1e-3), "unit": "pixels/s", "ms_per_step": w3,
                  "roofline": alu_roofline(k3, alu_ops16, "xdl16", k16), "launch": i3}
+        w4, k4, i4 = timed(rinr.FLAG_FP16_ALL)
+        alt16a = {"mode": "RINR_FLAG_FP16_ALL (opt-in, reduced precision: fp16 weights and activations in the hidden layers)",
+                  "value": pixels / (w4 * 1e-3), "unit": "pixels/s", "ms_per_step": w4,
+                  "roofline": alu_roofline(k4, alu_ops16a, "xdl16all", k16a), "launch": i4}
     assert st.status() == 0
 
     res = {
@@ -277,6 +289,8 @@ def main() -> int:
         res["fp32_mfma_mode"] = alt
     if alt16 is not None:
         res["fp16_act_mode"] = alt16
+    if alt16a is not None:
+        res["fp16_all_mode"] = alt16a
 
     if not args.no_cpu_baseline:
         from oracle import oracle

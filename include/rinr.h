@@ -128,7 +128,7 @@ enum { RINR_FLAG_NO_CLAMP = 1,     /* fp32 output only: write the linear output 
                                       accumulate); same results within the stated tolerance  */
        RINR_FLAG_NORMALIZE = 4,    /* fp32 output only: out = value * norm_scale[c] + norm_shift[c]
                                       per channel c, after the clamp                          */
-       RINR_FLAG_FP16_ACT = 8 };   /* faster, less precise: activations travel between layers as one
+       RINR_FLAG_FP16_ACT = 8,     /* faster, less precise: activations travel between layers as one
                                       fp16 value (relative rounding 2^-12 each) instead of a hi+lo
                                       pair; weights, coordinates and accumulation as in the default
                                       kernel.  Measured max-abs error against the fp64 definition:
@@ -138,6 +138,11 @@ enum { RINR_FLAG_NO_CLAMP = 1,     /* fp32 output only: write the linear output 
                                       gain and has no model-independent bound.  Ignored together
                                       with RINR_FLAG_FP32_MFMA, and where the store is served by the
                                       fp32 kernels anyway (operands beyond fp16 range)            */
+       RINR_FLAG_FP16_ALL = 16 };  /* fastest, least precise: RINR_FLAG_FP16_ACT, and the hidden layers'
+                                      weights are rounded to fp16 as well (after dequantisation and the
+                                      w0 scaling): fp16 operands with fp32 accumulation throughout the
+                                      hidden layers; the first and the last layer keep their hi+lo
+                                      pairs.  About 1.4 times the error of RINR_FLAG_FP16_ACT.          */
 
 /* Augmentation on the GPU, fused into the decode (Sec. III-B: decoded images are augmented
  * on the GPU before they reach the backbone).  Geometric augmentation (flip, crop + resize,

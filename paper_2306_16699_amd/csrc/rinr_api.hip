@@ -37,7 +37,7 @@ typedef void (*debug_fn)(const uint8_t *, int64_t, int, uint32_t, float *, float
 
 struct ClassImpl {
     decode_fn decode;      // fp32 MFMA kernel
-    decode_fn decode_xdl[6];  // split-precision fp16 MFMA kernel, per kind of hidden layers (kHiddenAllInt, AllRaw, Mixed); + 3: fp16 activations
+    decode_fn decode_xdl[7];  // split-precision fp16 MFMA kernel, per kind of hidden layers (kHiddenAllInt, AllRaw, Mixed); + 3: fp16 activations; 6: all fp16
     debug_fn debug;
     int (*total)(int L);   // expanded floats for L layers (fp32 kernel)
 };
@@ -47,12 +47,14 @@ template <int TM, int WP> ClassImpl make_impl() {
     return ClassImpl{decode_kernel<TM, WP, kThreads>,
                      {decode_xdl_kernel<WP / 16, kThreads, kHiddenAllInt>, decode_xdl_kernel<WP / 16, kThreads, kHiddenAllRaw>,
                       decode_xdl_kernel<WP / 16, kThreads, kHiddenMixed>, decode_xdl_kernel<WP / 16, kThreads, kHiddenAllInt | kAct16>,
-                      decode_xdl_kernel<WP / 16, kThreads, kHiddenAllRaw | kAct16>, decode_xdl_kernel<WP / 16, kThreads, kHiddenMixed | kAct16>},
+                      decode_xdl_kernel<WP / 16, kThreads, kHiddenAllRaw | kAct16>, decode_xdl_kernel<WP / 16, kThreads, kHiddenMixed | kAct16>,
+                      decode_xdl_kernel<WP / 16, kThreads, kAct16 | kWeight16>},
                      dequant_debug_kernel<TM, WP>,
                      total_of<TM, WP>};
 }
 
-const void *xdl_any_fn(int kind, bool act16 = false) {
+const void *xdl_any_fn(int kind, bool act16 = false, bool all16 = false) {
+    if (all16) return (const void *)decode_xdl_any_kernel<kThreads, kAct16 | kWeight16>;
     if (act16) {
         switch (kind) {
             case kHiddenAllInt: return (const void *)decode_xdl_any_kernel<kThreads, kHiddenAllInt | kAct16>;
@@ -258,6 +260,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
             hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[3], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
             hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[4], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
             hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[5], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+            hip_fail(hipFuncSetAttribute((const void *)im.decode_xdl[6], hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
             hip_fail(hipFuncSetAttribute((const void *)im.debug, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
             delete s;
             return RINR_E_HIP;
@@ -270,6 +273,7 @@ extern "C" int rinr_store_open(const void *device_blob, const void *host_blob, s
         hip_fail(hipFuncSetAttribute(xdl_any_fn(kHiddenAllInt, true), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute(xdl_any_fn(kHiddenAllRaw, true), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute(xdl_any_fn(kHiddenMixed, true), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
+        hip_fail(hipFuncSetAttribute(xdl_any_fn(0, true, true), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<16, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit)) ||
         hip_fail(hipFuncSetAttribute((const void *)decode_any_kernel<32, kThreads>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit))) {
         delete s;
@@ -321,7 +325,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (n < 0 || H <= 0 || W <= 0) return RINR_E_ARG;
     const int dt = opts->out_dtype;
     if (dt != RINR_OUT_F32 && dt != RINR_OUT_U8 && dt != RINR_OUT_F32_AND_U8) return RINR_E_ARG;
-    if (opts->flags & ~(RINR_FLAG_NO_CLAMP | RINR_FLAG_FP32_MFMA | RINR_FLAG_NORMALIZE | RINR_FLAG_FP16_ACT)) return RINR_E_ARG;
+    if (opts->flags & ~(RINR_FLAG_NO_CLAMP | RINR_FLAG_FP32_MFMA | RINR_FLAG_NORMALIZE | RINR_FLAG_FP16_ACT | RINR_FLAG_FP16_ALL)) return RINR_E_ARG;
     if ((opts->flags & RINR_FLAG_NORMALIZE) && dt != RINR_OUT_F32) return RINR_E_ARG;
     if (opts->flags & RINR_FLAG_NORMALIZE)
         for (int c = 0; c < 3; ++c)
@@ -372,14 +376,15 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     const bool want_fp32 = (opts->flags & RINR_FLAG_FP32_MFMA) || g_force_fp32;
     if (want_fp32 && !s->fp32_ok) return RINR_E_UNSUPPORTED;
     const bool xdl = s->xdl_ok && !want_fp32;
-    const bool act16 = xdl && (opts->flags & RINR_FLAG_FP16_ACT);
-    const int xk = s->hidden_kind + (act16 ? 3 : 0);      // index into ClassImpl::decode_xdl
+    const bool all16 = xdl && (opts->flags & RINR_FLAG_FP16_ALL);
+    const bool act16 = xdl && (opts->flags & (RINR_FLAG_FP16_ACT | RINR_FLAG_FP16_ALL));
+    const int xk = all16 ? 6 : s->hidden_kind + (act16 ? 3 : 0);      // index into ClassImpl::decode_xdl
 
     const uint32_t tiles = (uint32_t)((HW + 63) >> 6);
     const int threads = g_threads ? g_threads : (tiles >= 96 ? 768 : (tiles >= 64 ? 512 : 256));
     const uint32_t nw = (uint32_t)threads / 64;
 
-    const int knob = g_blocks_per_cu * 4 + (xdl ? 1 : 0) + (act16 ? 2 : 0);
+    const int knob = g_blocks_per_cu * 8 + (xdl ? 1 : 0) + (act16 ? 2 : 0) + (all16 ? 4 : 0);
     const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads && s->plan_knob == knob);
     for (uint32_t c = 1; c <= kMaxClass; ++c) a.stage_off[c] = xdl ? s->xdl_stage_off[c] : s->stage_off[c];
     int n_classes = 0;
@@ -393,7 +398,7 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     if (n_classes != 1) {
         // ragged store: one grid over all slots, each workgroup runs the body of its slot's class
         // (an empty store also comes here: every id is out of range and its slot is zero-filled)
-        const void *fn = xdl ? xdl_any_fn(s->hidden_kind, act16)
+        const void *fn = xdl ? xdl_any_fn(s->hidden_kind, act16, all16)
                              : (s->tile_rows_wide == 32 ? (const void *)decode_any_kernel<32, kThreads>
                                                         : (const void *)decode_any_kernel<16, kThreads>);
         uint32_t lds_bytes = 0;

@@ -45,6 +45,10 @@ enum { kHiddenAllInt = 0, kHiddenAllRaw = 1, kHiddenMixed = 2 };
 // Added to the kind: activations travel as one fp16 value instead of a hi+lo pair (RINR_FLAG_FP16_ACT): one MFMA
 // term less per layer and a two-instruction epilogue, at 2^-12 relative rounding per activation.
 enum { kAct16 = 4 };
+// Added to kAct16 (the kind is then irrelevant): the hidden layers' weights are single fp16 values too, fp16(w * w0 / 2pi)
+// whether the layer is stored as codes or as fp32, so every hidden layer is one MFMA term and its epilogue is
+// sine + conversion (RINR_FLAG_FP16_ALL): fp16 operands with fp32 accumulation throughout the hidden layers.
+enum { kWeight16 = 8 };
 
 struct XLayer {            // one entry per linear layer, built in LDS by the workgroup
     uint32_t off_hi;       // byte offset of the fp16 operand block
@@ -108,7 +112,7 @@ __host__ __device__ inline uint32_t xdl_model_bytes(int cls, int n_layers, int n
            wp * wp * 2u * (uint32_t)(n_int + 2 * n_raw) + 2u * out;
 }
 
-template <int TM, int WP>
+template <int TM, int WP, bool W16>
 __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec, int L, float pre, int tid, int nthreads,
                                                  uint32_t total_bytes) {
     typedef XLayout<TM, WP> LY;
@@ -128,6 +132,7 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
             e.off_lo = 0;
             if (l == 0) cur += LY::FIRST;
             else if (l == L - 1) { e.off_lo = cur + LY::OUT; cur += 2 * LY::OUT; }
+            else if (W16) cur += LY::HID;
             else if (xdl_int_layer(r.bits, r.scale * pre)) { e.scale = r.scale * pre; cur += LY::HID; }
             else { e.off_lo = cur + LY::HID; cur += 2 * LY::HID; }
             tab[l] = e;
@@ -160,6 +165,9 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
                                  hi[LY::idx_first(q, o, 4 + i)] = lw;     // low weight part x high coordinate half
                              }
                          },
+                         [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre; });
+        } else if (W16) {
+            expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { hi[LY::idx_hidden(o, i)] = (_Float16)(v * pre); },
                          [=](int o, float v) { bt[LY::idx_bias(o)] = v * pre; });
         } else if (e.off_lo == 0) {
             const float inv = 1.0f / e.scale;
@@ -331,8 +339,9 @@ __device__ __forceinline__ void xdl_layer(XHalf<TM, WP> &X, XHalf<TM, WP> &Y, co
 
 template <int TM, int WP, int MODE_>
 __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, float *lds_f) {
-    constexpr int MODE = MODE_ & 3;
-    constexpr bool A16 = (MODE_ & kAct16) != 0;
+    constexpr bool W16 = (MODE_ & kWeight16) != 0;
+    constexpr int MODE = W16 ? (int)kHiddenAllRaw : (MODE_ & 3);      // all-fp16: one form for every hidden layer, no scale
+    constexpr bool A16 = (MODE_ & kAct16) != 0 || W16;
     typedef XLayout<TM, WP> LY;
     typedef XTile<TM> T;
     typedef typename T::acc_t acc_t;
@@ -354,7 +363,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     // Tiles are handed out through a counter in LDS (it reuses the first word of the staging area,
     // which is dead once the model is expanded): the SIMD arbiter favours its older wavefront, so
     // with a fixed split the favoured waves would finish early and leave the others running alone.
-    xdl_expand_model<TM, WP>(lds, stage, L, a.pre, tid, nthreads, a.stage_off[WP / 16] << 2);
+    xdl_expand_model<TM, WP, W16>(lds, stage, L, a.pre, tid, nthreads, a.stage_off[WP / 16] << 2);
     uint32_t *next_tile = stage;
     if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
     __syncthreads();
@@ -427,7 +436,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
             if constexpr (MODE == kHiddenAllInt) {
                 xdl_layer<TM, WP, false, A16>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
             } else if constexpr (MODE == kHiddenAllRaw) {
-                xdl_layer<TM, WP, true, A16>(X, Y, lds, el, ll, ll / TM, 1.0f, 1.0f, neg1);
+                xdl_layer<TM, WP, !W16, A16>(X, Y, lds, el, ll, ll / TM, 1.0f, 1.0f, neg1);
             } else {
                 if (el.off_lo == 0) xdl_layer<TM, WP, false, A16>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);
                 else xdl_layer<TM, WP, true, A16>(X, Y, lds, el, ll, ll / TM, scale_prev, el.scale, neg1);

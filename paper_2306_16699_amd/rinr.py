@@ -21,6 +21,7 @@ FLAG_NO_CLAMP = 1
 FLAG_FP32_MFMA = 2
 FLAG_NORMALIZE = 4
 FLAG_FP16_ACT = 8
+FLAG_FP16_ALL = 16
 E_NULL, E_ARG, E_MODEL, E_SIZE, E_FORMAT, E_UNSUPPORTED, E_ALIGN, E_HIP = -1, -2, -3, -4, -5, -6, -7, -8
 
 EXPORTS = ["rinr_pack_size", "rinr_pack", "rinr_unpack_layer", "rinr_store_open", "rinr_store_close",

@@ -17,7 +17,7 @@ def tol_of(mode):
     """The opt-in single-fp16-activation mode rounds every hidden activation to 11 significant bits
     (error up to 2^-12 each); the 40x output layer used here multiplies that (about 2e-3 observed).
     Bar for that mode on these models: one step of the 8-bit output."""
-    return 1.0 / 255.0 if mode & rinr.FLAG_FP16_ACT else TOL
+    return 1.0 / 255.0 if mode & (rinr.FLAG_FP16_ACT | rinr.FLAG_FP16_ALL) else TOL
 
 
 def image_like(models, gain=40.0):
@@ -54,7 +54,7 @@ def test_augmented_decode_matches_oracle(k, n, H, W):
     ref = oracle.decode(models, w.image_ids, H, W, affine=aff.astype(np.float64), norm=(norm[0].astype(np.float64), norm[1].astype(np.float64)))
     ref_geo = oracle.decode(models, w.image_ids, H, W, affine=aff.astype(np.float64), clamp=False)
     gain_n = float(np.abs(norm[0]).max())          # the normalisation scales the error with the value
-    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT):
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL):
         got = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode, affine=aff_d, norm=norm).cpu().numpy()
         assert np.abs(got - ref).max() <= tol_of(mode) * gain_n, (mode, np.abs(got - ref).max())
         geo = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP, affine=aff_d).cpu().numpy()
@@ -73,7 +73,7 @@ def test_identity_map_and_unit_normalisation_change_nothing():
     st = rinr.Store(rinr.pack(image_like(w.models)))
     ids = torch.from_numpy(w.image_ids).cuda()
     ident = torch.tensor([[1, 0, 0, 0, 1, 0]] * 6, dtype=torch.float32, device="cuda")
-    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT):
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL):
         a = st.decode_batch_ex(ids, 20, 27, rinr.OUT_F32, mode).cpu().numpy()
         b = st.decode_batch_ex(ids, 20, 27, rinr.OUT_F32, mode, affine=ident, norm=((1, 1, 1), (0, 0, 0))).cpu().numpy()
         assert np.array_equal(a, b)
@@ -115,6 +115,6 @@ def test_augmentation_argument_errors():
     o = rinr.DecodeOpts(rinr.OUT_F32, 0, None)
     o.affine = aff.data_ptr() + 2
     assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ALIGN
-    o = rinr.DecodeOpts(rinr.OUT_F32, 16, None)                     # an unknown flag bit
+    o = rinr.DecodeOpts(rinr.OUT_F32, 32, None)                     # an unknown flag bit
     assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ARG
     st.close()

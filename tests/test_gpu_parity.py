@@ -57,7 +57,7 @@ def check_workload(torch, w, models=None, tile=DEFAULT_TILE, u8=False):
     ref_nc = oracle.decode(models, w.image_ids, w.H, w.W, w.w0, w.coord_lo, w.coord_hi, clamp=False)
     ref, ref8 = oracle.decode(models, w.image_ids, w.H, w.W, w.w0, w.coord_lo, w.coord_hi, want_u8=True)
     worst = 0.0
-    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT):
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL):
         got_nc = st.decode_batch_ex(ids, w.H, w.W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy().astype(np.float64)
         err_nc = np.abs(got_nc - ref_nc).max()
         assert err_nc <= TOL, f"mode {mode}: unclamped max-abs {err_nc}"
@@ -307,7 +307,7 @@ def test_store_open_validates_on_device_copy(torch):
     st = rinr.Store(rinr.pack(most))
     assert st.info() == (2, 64, 16)
     ref = oracle.decode(most, [0, 1], 13, 10, clamp=False)
-    for mode in (0, rinr.FLAG_FP16_ACT):
+    for mode in (0, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL):
         got = st.decode_batch_ex(ids_dev(torch, [0, 1]), 13, 10, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy()
         assert np.abs(got - ref).max() <= TOL, mode
     st.close()
@@ -355,7 +355,7 @@ def test_heaviest_first_order_changes_nothing(torch):
     ids_h[[3, 77, 299]] = [-1, 500, 2 ** 40]
     ids = torch.from_numpy(ids_h).cuda()
     ws = torch.empty(rinr.workspace_bytes(300), dtype=torch.uint8, device="cuda")
-    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT):
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL):
         a = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode)
         b = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode, workspace=ws)
         assert torch.equal(a, b), mode
@@ -364,9 +364,9 @@ def test_heaviest_first_order_changes_nothing(torch):
         cost = np.array([0 if not (0 <= i < 500) else (len(w.models[int(i)].layers)) *
                          {1: 3, 2: 6, 3: 10, 4: 13}[(max(ly.n_out for ly in w.models[int(i)].layers[:-1]) + 15) // 16] for i in ids_h])
         assert np.all(np.diff(cost[order]) <= 0)                            # ... by falling cost
-        f32, u8 = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32_AND_U8, mode & ~rinr.FLAG_FP16_ACT, workspace=ws)
-        assert torch.equal(f32, st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode & ~rinr.FLAG_FP16_ACT))
-    assert st.status() == 3 * 4 * 3                 # three bad ids in each of the four decodes per mode
+        f32, u8 = st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32_AND_U8, mode & rinr.FLAG_FP32_MFMA, workspace=ws)
+        assert torch.equal(f32, st.decode_batch_ex(ids, 24, 37, rinr.OUT_F32, mode & rinr.FLAG_FP32_MFMA))
+    assert st.status() == 3 * 4 * 4                 # three bad ids in each of the four decodes per mode
     # too small a workspace, a misaligned one
     L = rinr.lib()
     out = torch.empty((300, 3, 24, 37), device="cuda")
@@ -402,4 +402,4 @@ def test_heaviest_first_order_changes_nothing(torch):
 
 
 def test_zz_report_worst_errors():
-    print("largest unclamped max-abs error per mode:", {("default" if m == 0 else "fp32 MFMA" if m == rinr.FLAG_FP32_MFMA else "fp16 activations"): f"{e:.2e}" for m, e in WORST.items()})
+    print("largest unclamped max-abs error per mode:", {{0: "default", rinr.FLAG_FP32_MFMA: "fp32 MFMA", rinr.FLAG_FP16_ACT: "fp16 activations", rinr.FLAG_FP16_ALL: "fp16 weights and activations"}[m]: f"{e:.2e}" for m, e in WORST.items()})
