@@ -202,6 +202,21 @@ def test_small_and_ragged_grids(torch, H, W):
     check_workload(torch, w, models=image_like(w.models), u8=True)
 
 
+@pytest.mark.parametrize("H,W", [(1201, 1999), (1024, 2048)])
+def test_few_large_images(torch, H, W):
+    """Millions of pixels per image: many workgroups per slot, pixel indices far beyond one tile row, W a power of
+    two and not (the row/column split of a pixel index is a multiply-high by a constant made from W)."""
+    w = synth.workload(1, n_images=2, H=H, W=W)
+    st = rinr.Store(rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi))
+    ids = ids_dev(torch, w.image_ids)
+    ref = oracle.decode(w.models, w.image_ids, H, W, w.w0, w.coord_lo, w.coord_hi, clamp=False)
+    for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ALL):
+        got = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP).cpu().numpy()
+        assert np.abs(got - ref).max() <= TOL, mode
+        assert st.last_launch_info()["workgroups"] > 2
+    st.close()
+
+
 def test_resolution_free_decode(torch):
     """Same store decoded at several resolutions (Sec. III-B): nested pixel-centre grids agree."""
     w = synth.workload(3, n_images=3, H=10, W=12)
