@@ -38,11 +38,12 @@ constexpr int fit_tiles(int wq) { return (wq + 15) / 16; }
 // Wavefronts per workgroup (= per image).  Every phase between two barriers is a short dependent chain per
 // wavefront, so what fills the matrix pipe is other wavefronts: 4 at widths <= 16, whose 4 tiles per layer do not feed
 // more, and several images per CU; 8 at widths <= 32, two images per CU; 12 at widths <= 48, one wavefront per tile of
-// their 12-tile layers (LDS holds one image); 8 above.
-constexpr int fit_waves(int wq) { return fit_tiles(wq) == 1 ? 4 : (fit_tiles(wq) == 3 ? 12 : 8); }
+// their 12-tile layers (LDS holds one image); 16 above, one per forward tile, so that the 20 gradient tiles of a
+// width-64 layer take two rounds instead of three (+3 %, a few spilled registers notwithstanding).
+constexpr int fit_waves(int wq) { return fit_tiles(wq) == 1 ? 4 : (fit_tiles(wq) == 2 ? 8 : (fit_tiles(wq) == 3 ? 12 : 16)); }
 // Wavefronts per SIMD the kernel is compiled for (the register budget follows): at widths <= 32 two workgroups
 // share a CU (10 x 32 at 224 x 224, 512 images: 26.8 -> 20.3 ms per step).
-constexpr int fit_waves_per_simd(int wq) { return fit_tiles(wq) == 1 ? 3 : (fit_tiles(wq) == 2 ? 4 : (fit_tiles(wq) == 3 ? 3 : 2)); }
+constexpr int fit_waves_per_simd(int wq) { return fit_tiles(wq) == 1 ? 3 : (fit_tiles(wq) == 3 ? 3 : 4); }
 // Layer counts the kernels are built for: the accumulators of all layers stay in registers, so the depth
 // is a compile-time bound and a shallow model takes the kernel with the smaller one.
 constexpr int fit_depth_lo(int wq) { return fit_tiles(wq) == 1 ? 4 : (fit_tiles(wq) == 4 ? 7 : 10); }
