@@ -77,6 +77,7 @@ inline bool hip_fail(hipError_t e) {
 //   B0, B1, B2 [KR rows] three pixel buffers.  Forward: the input of layer l is B[l & 1] (row 0 ones, rows 4.. the
 //       activations; B0 rows 1..3 hold x, y, 0).  Backward: B0 holds the restored input of the layer at hand; B1 / B2
 //       the back-propagated error with row = unit, ping-pong (so B1's row of ones is written again for every chunk).
+//   B3 [KR rows]       with PIPE: the restored layer inputs alternate between B0 and B3.
 // Pre-activations are not stashed in LDS: the wavefront that computed a tile keeps it in registers until the
 // backward pass has used it (sine again for the weight gradient's operand, cosine for the error).
 template <int WQ> struct Shape {
@@ -94,7 +95,10 @@ template <int WQ> struct Shape {
     static __host__ __device__ constexpr int w_off(int l) { return l == 0 ? 0 : RO * 6 + (l - 1) * RO * LD; }
     static __host__ __device__ constexpr int w_end(int L) { return RO * 6 + (L - 2) * RO * LD + 16 * LD; }
     static __host__ __device__ constexpr int buf(int b, int L) { return w_end(L) + b * prow(KR); }
-    static __host__ __device__ constexpr int total(int L) { return buf(3, L); }
+    // A fourth buffer, where LDS has room for it (one image per CU at widths 33..48, small models at widths <= 16):
+    // the backward pass then restores the next layer's input while it works on this one, one barrier less per layer.
+    static constexpr bool PIPE = MT == 1 || MT == 3;
+    static __host__ __device__ constexpr int total(int L) { return buf(PIPE ? 4 : 3, L); }
 };
 
 struct FitArgs {
@@ -164,7 +168,9 @@ __global__ __launch_bounds__(Shape<WQ>::NTHREADS, fit_waves_per_simd(WQ)) void f
     const size_t img = blockIdx.x;
     float *P = a.params + img * a.n_params;
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    constexpr bool PIPE = S::PIPE;
     float *const B0 = lds + S::buf(0, a.L), *const B1 = lds + S::buf(1, a.L), *const B2 = lds + S::buf(2, a.L);
+    float *const B3 = PIPE ? lds + S::buf(3, a.L) : B0;
 
     // ---- set up: zero everything, then the weights (sine layers times w0 / 2pi) behind their bias column
     for (int q = tid; q < S::total(a.L); q += kThreads) lds[q] = 0.0f;
@@ -177,6 +183,7 @@ __global__ __launch_bounds__(Shape<WQ>::NTHREADS, fit_waves_per_simd(WQ)) void f
         for (int e = tid; e < dout * din; e += kThreads) Wt[(e / din) * ld + first + e % din] = src[e] * sc;
         for (int o = tid; o < dout; o += kThreads) Wt[o * ld] = src[dout * din + o] * sc;
     }
+    if (PIPE && tid < PC) B3[S::prow(0) + tid] = 1.0f;       // its row of ones; nothing else ever writes its rows 0..3
     __syncthreads();
 
     f32x4 acc[ML][GSLOTS];          // weight-gradient tiles, whole step
@@ -251,32 +258,41 @@ __global__ __launch_bounds__(Shape<WQ>::NTHREADS, fit_waves_per_simd(WQ)) void f
                 __syncthreads();
             }
         }
-        // ---- backward, layer by layer: restore H_l into B0; then dW_l += E_l H_l^T into this wavefront's
-        //      accumulators (tile rows ot, columns it) and E_{l-1} = (W_l^T E_l) * cos(2pi z_{l-1}) (tile rows it, pixels nt)
+        // ---- backward, layer by layer: restore H_l (the layer's input); then dW_l += E_l H_l^T into this wavefront's
+        //      accumulators (tile rows ot, columns it) and E_{l-1} = (W_l^T E_l) * cos(2pi z_{l-1}) (tile rows it, pixels nt).
+        //      With PIPE only the first of these layers restores its own input ahead; every layer restores the next one's
+        //      into the other H buffer while it computes.
+        auto restore = [&](int l, float *H) {          // l is a constant after unrolling
+            if (l == 0) {
+                put_coords(c);                         // B0, which is where layer 0's input is expected
+            } else {
+#pragma unroll
+                for (int s = 0; s < ZSLOTS; ++s) {
+                    const int task = wave + s * kWaves;
+                    if (task < MT * PT) {
+                        const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) H[S::prow(4 + mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v]);
+                    }
+                }
+            }
+        };
         float *Dc = B2, *Dn = B1;
 #pragma unroll
         for (int l = ML - 1; l >= 0; --l) {
             if (l < L) {
                 const bool last = l == L - 1;
-                if (l == 0) {
-                    put_coords(c);
-                } else {
-#pragma unroll
-                    for (int s = 0; s < ZSLOTS; ++s) {
-                        const int task = wave + s * kWaves;
-                        if (task < MT * PT) {
-                            const int mt = task / PT, nt = task - mt * PT, col = nt * 16 + m;
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) B0[S::prow(4 + mt * 16 + 4 * kq + v) + col] = __builtin_amdgcn_sinf(zst[l - 1][s][v]);
-                        }
-                    }
+                float *const Hc = (PIPE && (l & 1)) ? B3 : B0;      // holds H_l
+                float *const Hn = (PIPE && !(l & 1)) ? B3 : B0;     // PIPE: receives H_{l-1}
+                if (!PIPE || last) {
+                    restore(l, Hc);
+                    __syncthreads();
                 }
-                __syncthreads();
                 if (l == 0) {
 #pragma unroll
                     for (int s = 0; s < GSLOTS; ++s) {
                         const int ot = wave + s * kWaves;        // columns ones, x, y; the other lanes read the zero row
-                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(m < 4 ? m : 3) + kq, acc[0][s]);
+                        if (ot < MT) acc[0][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, Hc + S::prow(m < 4 ? m : 3) + kq, acc[0][s]);
                     }
                 } else {
                     const int ntasks = (last ? 1 : MT) * NIT;
@@ -285,8 +301,8 @@ __global__ __launch_bounds__(Shape<WQ>::NTHREADS, fit_waves_per_simd(WQ)) void f
                         const int task = wave + s * kWaves;
                         if (task < ntasks) {
                             const int ot = task / NIT, it = task - ot * NIT, i = it * 16 + m;
-                            // columns beyond the buffer's rows read B0's zero row
-                            acc[l][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, B0 + S::prow(i < KR ? i : 3) + kq, acc[l][s]);
+                            // columns beyond the buffer's rows read the buffer's zero row
+                            acc[l][s] = contract<PC / 4, 4, 4, false>(Dc + S::prow(ot * 16 + m) + kq, Hc + S::prow(i < KR ? i : 3) + kq, acc[l][s]);
                         }
                     }
                     const float *Wt = lds + S::w_off(l);
@@ -302,6 +318,7 @@ __global__ __launch_bounds__(Shape<WQ>::NTHREADS, fit_waves_per_simd(WQ)) void f
                                 Dn[S::prow(it * 16 + 4 * kq + v) + col] = g[v] * __builtin_amdgcn_cosf(zst[l - 1][s][v]);
                         }
                     }
+                    if (PIPE) restore(l - 1, Hn);
                 }
                 __syncthreads();
                 float *t = Dc;
