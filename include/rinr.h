@@ -161,7 +161,8 @@ typedef struct {
     void *workspace;         /* device, 4-byte aligned, or NULL.  Scratch for one call: with it, a batch from
                                 a store that mixes model widths or depths is decoded heaviest model first (one
                                 more small kernel orders the slots), which shortens the tail of the grid;
-                                results are the same bytes.  Calls that may overlap need their own.    */
+                                results are the same bytes.  Calls that may overlap need their own.
+                                The ordering kernel is one workgroup: about 6 us per thousand slots.   */
     size_t workspace_bytes;  /* >= rinr_decode_workspace_bytes(n), else RINR_E_SIZE                    */
 } rinr_decode_opts;
 
