@@ -75,7 +75,8 @@ typedef struct rinr_fit rinr_fit;
 /* Device state for fitting n_images models of one architecture to H x W targets: parameters,
  * Adam moments, keep flags and per-image losses (3 * 4 + 1 bytes per parameter).  All images share
  * the architecture; each has its own parameters.  RINR_E_ARG for a bad architecture or size,
- * RINR_E_UNSUPPORTED if the model's working set exceeds one CU's LDS, RINR_E_HIP. */
+ * RINR_E_UNSUPPORTED if the model is deeper than the kernels are built for (widest hidden layer <= 32: 12 linear
+ * layers, <= 48: 10, <= 64: 7; the weights of all layers stay in one CU's LDS and the gradients in registers), RINR_E_HIP. */
 int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, rinr_fit **fit);
 int rinr_fit_destroy(rinr_fit *fit);
 int64_t rinr_fit_n_params(const rinr_fit *fit);        /* per image; < 0 on NULL */
