@@ -225,6 +225,16 @@ def test_fit_argument_errors_and_empty():
     assert e.value.code == rinr.E_ARG
     with pytest.raises(rinr.RinrError):
         rinr_fit.Fit([2, 8, 3], 1, 0, 4)
+    # depth limits per width: 12 linear layers up to width 32, 10 up to 48, 7 up to 64
+    for widths, ok in (([2] + [32] * 11 + [3], True), ([2] + [33] * 11 + [3], False), ([2] + [48] * 9 + [3], True),
+                       ([2] + [48] * 10 + [3], False), ([2] + [64] * 6 + [3], True), ([2] + [64] * 7 + [3], False),
+                       ([2] + [8] * 12 + [3], False)):
+        if ok:
+            rinr_fit.Fit(widths, 1, 4, 4).close()
+        else:
+            with pytest.raises(rinr.RinrError) as e:
+                rinr_fit.Fit(widths, 1, 4, 4)
+            assert e.value.code in (rinr.E_UNSUPPORTED, rinr.E_ARG), widths
     f = rinr_fit.Fit([2, 8, 3], 0, 4, 4)
     f.steps(torch.empty((0, 3, 4, 4), device="cuda"), 3, 1e-3)
     assert f.get_params().shape == (0, f.n_params)
