@@ -280,7 +280,15 @@ __global__ __launch_bounds__(1024) void order_slots_kernel(const uint8_t *blob, 
     const uint32_t tid = threadIdx.x;
     if (tid < (uint32_t)kOrderKeys) cursor[tid] = 0u;
     __syncthreads();
-    for (uint32_t s = tid; s < n; s += 1024u) atomicAdd(&cursor[order_key(blob, n_models, ids[s])], 1u);
+    // four slots per thread and round, so that their id and index reads are in flight together
+    for (uint32_t s0 = tid; s0 < n; s0 += 4096u) {
+        uint32_t key[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) key[u] = s0 + 1024u * u < n ? order_key(blob, n_models, ids[s0 + 1024u * u]) : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (s0 + 1024u * u < n) atomicAdd(&cursor[key[u]], 1u);
+    }
     __syncthreads();
     if (tid == 0) {
         uint32_t at = 0;
@@ -291,7 +299,14 @@ __global__ __launch_bounds__(1024) void order_slots_kernel(const uint8_t *blob, 
         }
     }
     __syncthreads();
-    for (uint32_t s = tid; s < n; s += 1024u) order[atomicAdd(&cursor[order_key(blob, n_models, ids[s])], 1u)] = s;
+    for (uint32_t s0 = tid; s0 < n; s0 += 4096u) {
+        uint32_t key[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) key[u] = s0 + 1024u * u < n ? order_key(blob, n_models, ids[s0 + 1024u * u]) : 0u;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (s0 + 1024u * u < n) order[atomicAdd(&cursor[key[u]], 1u)] = s0 + 1024u * u;
+    }
 }
 
 // ---- gather: workgroup -> (slot, tile range); slot -> id -> index entry (Sec. III-B batch select).
