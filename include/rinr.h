@@ -216,7 +216,9 @@ int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
  * knob 1: 0 = split each slot's pixels over workgroups by the built-in cost model; else a
  *         fixed grid target in workgroups per compute unit (1..1024).
  * knob 2: threads per workgroup: 0 = by image size, or a multiple of 64 up to 768.
- * knob 3: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA). */
+ * knob 3: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA).
+ * knob 4: stores that mix width classes decode images of at least this many 64-pixel tiles in one grid, smaller ones
+ *         class by class (default 64). */
 int rinr_tune(int knob, int value);
 
 const char *rinr_strerror(int code);

@@ -31,6 +31,7 @@ int g_tile_rows_wide = 32;      // MFMA tile for classes 2 and 4: 16 (16x16x4) o
 int g_blocks_per_cu = 0;        // 0 = modelled split; else a fixed grid target in workgroups per CU
 int g_threads = 0;              // 0 = choose by image size, else a multiple of 64 up to kThreads
 int g_force_fp32 = 0;           // 1 = always use the fp32 MFMA kernel
+int g_any_min_tiles = 64;       // stores that mix width classes: images of fewer 64-pixel tiles are decoded class by class
 
 typedef void (*decode_fn)(const DecodeArgs);
 typedef void (*debug_fn)(const uint8_t *, int64_t, int, uint32_t, float *, float *);
@@ -152,6 +153,7 @@ extern "C" int rinr_tune(int knob, int value) {
         case 1: if (value < 0 || value > 1024) return RINR_E_ARG; g_blocks_per_cu = value; return RINR_OK;
         case 2: if (value != 0 && (value % 64 || value < 64 || value > kThreads)) return RINR_E_ARG; g_threads = value; return RINR_OK;
         case 3: if (value != 0 && value != 1) return RINR_E_ARG; g_force_fp32 = value; return RINR_OK;
+        case 4: if (value < 0) return RINR_E_ARG; g_any_min_tiles = value; return RINR_OK;
         default: return RINR_E_ARG;
     }
 }
@@ -384,18 +386,22 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
     const int threads = g_threads ? g_threads : (tiles >= 96 ? 768 : (tiles >= 64 ? 512 : 256));
     const uint32_t nw = (uint32_t)threads / 64;
 
-    const int knob = g_blocks_per_cu * 8 + (xdl ? 1 : 0) + (act16 ? 2 : 0) + (all16 ? 4 : 0);
-    const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads && s->plan_knob == knob);
-    for (uint32_t c = 1; c <= kMaxClass; ++c) a.stage_off[c] = xdl ? s->xdl_stage_off[c] : s->stage_off[c];
     int n_classes = 0;
     for (uint32_t c = 1; c <= kMaxClass; ++c) n_classes += s->sum.class_count[c] ? 1 : 0;
+    // a store that mixes width classes: one grid whose workgroups run the body of their slot's class, or, for images of
+    // few tiles, one launch per class with that class's LDS size (workgroups of other classes return at once)
+    // (an empty store also takes the one grid: every id is out of range and its slot is zero-filled)
+    const bool one_grid = n_classes == 0 || (n_classes > 1 && (int64_t)tiles >= (int64_t)g_any_min_tiles);
+    const int knob = g_blocks_per_cu * 16 + (xdl ? 1 : 0) + (act16 ? 2 : 0) + (all16 ? 4 : 0) + (one_grid ? 8 : 0);
+    const bool replan = !(s->plan_hw == HW && s->plan_n == n && s->plan_threads == threads && s->plan_knob == knob);
+    for (uint32_t c = 1; c <= kMaxClass; ++c) a.stage_off[c] = xdl ? s->xdl_stage_off[c] : s->stage_off[c];
 
     // slots of unequal cost are taken heaviest first when the caller gives the scratch for the order
     const bool order = opts->workspace && !s->even_cost;
     if (order) a.order = (const uint32_t *)opts->workspace;
     int launches = 0;
     uint32_t big_lds = 0, total_blocks = 0;
-    if (n_classes != 1) {
+    if (one_grid) {
         // ragged store: one grid over all slots, each workgroup runs the body of its slot's class
         // (an empty store also comes here: every id is out of range and its slot is zero-filled)
         const void *fn = xdl ? xdl_any_fn(s->hidden_kind, act16, all16)
@@ -445,12 +451,12 @@ extern "C" int rinr_decode_batch_ex(const rinr_store *s, const int64_t *image_id
             a.chunks = pl.chunks;
             a.tiles_per_chunk = pl.tiles_per_chunk;
             a.cls = c;
-            a.handle_bad = 1u;
-            if (order) RINR_HIP(order_slots(s, image_ids, n, opts->workspace, stream));
+            a.handle_bad = launches == 0 ? 1u : 0u;       // the first launch zero-fills and counts the out-of-range ids
+            if (order && launches == 0) RINR_HIP(order_slots(s, image_ids, n, opts->workspace, stream));
             hipLaunchKernelGGL(xdl ? im.decode_xdl[xk] : im.decode, dim3((uint32_t)n * pl.chunks), dim3((uint32_t)threads), lds_bytes,
                                (hipStream_t)stream, a);
             RINR_HIP(hipGetLastError());
-            launches = order ? 2 : 1;
+            launches += (order && launches == 0) ? 2 : 1;
             total_blocks = (uint32_t)n * pl.chunks;
             big_lds = lds_bytes;
         }
