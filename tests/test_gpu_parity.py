@@ -161,6 +161,23 @@ def test_parity_tile16_variant(torch, k, n, H, W):
     check_workload(torch, w, models=image_like(w.models), tile=16, u8=True)
 
 
+@pytest.mark.parametrize("threads,blocks_per_cu,any_min", [(256, 0, 64), (512, 3, 64), (768, 16, 64), (0, 1, 0), (0, 0, 1 << 20)])
+def test_parity_under_other_launch_shapes(torch, threads, blocks_per_cu, any_min):
+    """The planner picks threads per workgroup, workgroups per slot and, for stores of mixed width, one grid or class by
+    class from the image size: here they are forced, on a uniform and on a ragged workload."""
+    try:
+        rinr.tune(2, threads)
+        rinr.tune(1, blocks_per_cu)
+        rinr.tune(4, any_min)
+        check_workload(torch, synth.workload(3, n_images=6, H=70, W=83))
+        w = synth.workload(5, n_images=48, pool=300, H=72, W=65)
+        check_workload(torch, w, models=image_like(w.models), u8=True)
+    finally:
+        rinr.tune(2, 0)
+        rinr.tune(1, 0)
+        rinr.tune(4, 64)
+
+
 def test_parity_ragged_pool(torch):
     w = synth.workload(5, n_images=64, pool=400, H=40, W=37)
     assert len({(m.width, m.n_sine_layers) for m in w.models}) == 20
