@@ -24,19 +24,19 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak (256 CUs x 256 FLOP/clk x 2.4 GHz)
 PEAK_FP16_MFMA_TFLOPS = 2500.0    # MI355X dense fp16 matrix peak
-PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12   # 39.3 T lane-operations/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+# The method's own vector work is one sine per sine-layer output.  v_sin_f32 issues one wavefront instruction per
+# 8 clocks per SIMD (half the plain vector rate; measured): 256 CUs x 4 SIMDs x 64 lanes / 8 clocks x 2.4 GHz.
+PEAK_SINES_T = 256 * 4 * 64 / 8 * 2.4e9 / 1e12
 
 
-def alu_ops_per_pixel(model, act16: bool = False, all16: bool = False) -> float:
-    """Vector-ALU operations the split-precision path needs per pixel (algorithmic, one per lane):
-    per sine-layer output: sine, hi conversion (1/2), residual, lo conversion (1/2) = 3, plus the
-    dequantisation scale where the layer is stored as 2..8-bit codes (it multiplies the accumulator).
-    With a single fp16 value per activation (act16) the residual and its conversion go: sine + 1/2.
-    With fp16 weights as well (all16) the scale is folded into them: sine + 1/2 for every layer."""
-    n = 0.0
-    for l, ly in enumerate(model.layers[:-1]):
-        n += ly.n_out * ((1.5 if (act16 or all16) else 3) + (1 if (l > 0 and 2 <= ly.bits <= 8 and not all16) else 0))
-    return n
+def sines_per_pixel(model) -> int:
+    """Sine evaluations per pixel: one per output of every sine layer (all linear layers but the last)."""
+    return sum(ly.n_out for ly in model.layers[:-1])
+
+
+def nonzero_flop_per_pixel(model) -> int:
+    """2 x the number of kept (non-pruned) weights: what a decoder that skipped zeros would execute."""
+    return 2 * sum(int(ly.n_in * ly.n_out if ly.keep is None else np.count_nonzero(ly.keep)) for ly in model.layers)
 
 
 def host_threads() -> int:
@@ -160,17 +160,11 @@ def main() -> int:
     rinr.lib()
     if args.fit:
         return bench_fit(args)
-    if args.tile:
-        rinr.tune(0, args.tile)
-    if args.blocks_per_cu:
-        rinr.tune(1, args.blocks_per_cu)
-    if args.threads:
-        rinr.tune(2, args.threads)
 
     w = synth.paper_workload(args.paper, args.batch or None) if args.paper else synth.workload(args.config)
     args.config = args.paper or args.config
     blob = rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)
-    st = rinr.Store(blob)
+    st = rinr.Store(blob, fp32_tile_rows=args.tile)
     ids = torch.from_numpy(w.image_ids).cuda()
     n, H, W = w.n, w.H, w.W
     out = torch.empty((n, 3, H, W), dtype=torch.float32, device="cuda")
@@ -191,8 +185,10 @@ def main() -> int:
     workspace = torch.empty(rinr.workspace_bytes(n), dtype=torch.uint8, device="cuda")
 
     def timed(flags):
+        """(wall ms per step, kernel ms per step over exactly args.steps launches, per-launch min / median ms, launch info)."""
         def step():
-            st.decode_batch_ex(ids, H, W, dtype, flags, out=out, out_u8=out8, affine=affine, norm=norm, workspace=workspace)
+            st.decode_batch_ex(ids, H, W, dtype, flags, out=out, out_u8=out8, affine=affine, norm=norm, workspace=workspace,
+                               threads=args.threads, blocks_per_cu=args.blocks_per_cu)
         tw, done = time.perf_counter(), 0
         while done < args.warmup or (time.perf_counter() - tw) * 1e3 < args.min_warmup_ms:
             step()
@@ -208,66 +204,89 @@ def main() -> int:
         ev1.record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        return (t1 - t0) * 1e3 / args.steps, ev0.elapsed_time(ev1) / args.steps, st.last_launch_info()
+        # a second pass with an event between every two launches: the spread of single launches (not part of `value`)
+        k = min(args.steps, 200)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(k + 1)]
+        evs[0].record()
+        for i in range(k):
+            step()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        per = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(k)])
+        return (t1 - t0) * 1e3 / args.steps, ev0.elapsed_time(ev1) / args.steps, float(per.min()), float(np.median(per)), st.last_launch_info()
 
     pixels = n * H * W
-    flop_px = np.array([synth.dense_flop_per_pixel(w.models[int(i)]) for i in w.image_ids], dtype=np.float64)
-    flops = float(flop_px.sum()) * H * W
-    alu_px = np.array([alu_ops_per_pixel(w.models[int(i)]) for i in w.image_ids], dtype=np.float64)
-    alu_ops = float(alu_px.sum()) * H * W
-    alu_ops16 = float(sum(alu_ops_per_pixel(w.models[int(i)], True) for i in w.image_ids)) * H * W
-    alu_ops16a = float(sum(alu_ops_per_pixel(w.models[int(i)], True, True) for i in w.image_ids)) * H * W
+    used = [w.models[int(i)] for i in w.image_ids]
+    flop_px = np.array([synth.dense_flop_per_pixel(m) for m in used], dtype=np.float64)
+    flops = float(flop_px.sum()) * H * W                         # algorithmic: 2 x sum(in x out) per pixel with the true widths
+    nz_flops = float(sum(nonzero_flop_per_pixel(m) for m in used)) * H * W
+    sines = float(sum(sines_per_pixel(m) for m in used)) * H * W
+    out_bytes = pixels * (12 + (3 if out8 is not None else 0))
 
-    def traffic_of(tag):
+    def stored_traffic(tag):
         tpath = os.path.join(ROOT, "profiles", f"decode_{tag}_cfg{args.config}_traffic.json")
         if os.path.exists(tpath):
             try:
-                return json.load(open(tpath)).get("hbm_bytes_per_launch")
+                return json.load(open(tpath)).get("hbm_bytes_per_launch"), os.path.relpath(tpath, ROOT)
             except Exception:
-                return None
-        return None
+                return None, None
+        return None, None
 
-    def mfma_roofline(kern_ms, tag):
+    def roofline(t, peak, tag, kernel, executed_factor):
+        """The contraction's roofline: algorithmic FLOP per launch / mean launch duration against the dense matrix peak
+        of the dtype the contraction runs in."""
+        wall_ms, kern_ms, kmin, kmed, info = t
         ach = flops / (kern_ms * 1e-3) / 1e12
-        return {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_FP32_MFMA_TFLOPS, "traffic": traffic_of(tag), "kernel_ms": kern_ms,
-                "flop_per_launch": flops, "kernel": "decode_kernel (fp32 MFMA)"}
+        traffic, src = stored_traffic(tag)
+        return {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                "traffic": traffic,
+                "traffic_source": (f"stored figure from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), {src}; not measured in this run"
+                                   if traffic is not None else None),
+                "kernel_ms": kern_ms, "kernel_ms_min": kmin, "kernel_ms_median": kmed,
+                "flop_per_launch": flops, "flop_per_pixel_mean": float(flop_px.mean()),
+                "executed_over_algorithmic_flop": executed_factor, "kernel": kernel,
+                "nonzero_mac_tflops": nz_flops / (kern_ms * 1e-3) / 1e12,
+                "output_write_GBps": out_bytes / (kern_ms * 1e-3) / 1e9,
+                "vector_alu": {"bound": "alu", "work": "sine evaluations (one per sine-layer output per pixel)",
+                               "achieved": sines / (kern_ms * 1e-3) / 1e12, "peak": PEAK_SINES_T, "unit": "T sines/s",
+                               "frac": sines / (kern_ms * 1e-3) / 1e12 / PEAK_SINES_T, "sines_per_launch": sines}}
 
-    def alu_roofline(kern_ms, ops, tag, kernel):
-        ach = ops / (kern_ms * 1e-3) / 1e12
-        return {"bound": "alu", "achieved": ach, "peak": PEAK_VALU_TOPS, "unit": "Top/s (vector-ALU lane operations)",
-                "frac": ach / PEAK_VALU_TOPS, "traffic": traffic_of(tag), "kernel_ms": kern_ms,
-                "alu_ops_per_launch": ops, "kernel": kernel,
-                "matrix_algorithmic_tflops": flops / (kern_ms * 1e-3) / 1e12, "matrix_fp16_peak_tflops": PEAK_FP16_MFMA_TFLOPS}
+    def mode_entry(name, t, roof):
+        return {"mode": name, "value": pixels / (t[0] * 1e-3), "unit": "pixels/s", "ms_per_step": t[0], "roofline": roof, "launch": t[4]}
 
-    alt, alt16, alt16a = None, None, None
+    k32 = "decode_kernel (fp32 MFMA)"
+    kx = "decode_xdl_kernel (fp16 hi+lo operand pairs on the fp16 matrix cores, fp32 accumulate)"
     k16 = "decode_xdl_kernel, one fp16 value per activation (fp16 MFMA, fp32 accumulate)"
     k16a = "decode_xdl_kernel, fp16 weights and activations in the hidden layers (fp16 MFMA, fp32 accumulate)"
+    F16A = rinr.FLAG_FP16_ACT | rinr.FLAG_FP16_UNCHECKED
+    F16W = rinr.FLAG_FP16_ALL | rinr.FLAG_FP16_UNCHECKED
+    coded = all(2 <= ly.bits <= 8 for m in used[:64] for ly in m.layers[1:-1])
+    fx = 2.0 if coded else 3.0            # MFMA terms per algorithmic product: Q*hi + Q*lo, or Wh*hh + Wh*hl + Wl*hh
+    alt, alt16, alt16a = None, None, None
     if args.fp32_mfma:
-        wall_ms, kern_ms, info = timed(rinr.FLAG_FP32_MFMA)
-        roof, dtype_name = mfma_roofline(kern_ms, "fp32mfma"), "f32"
+        t = timed(rinr.FLAG_FP32_MFMA)
+        roof, dtype_name = roofline(t, PEAK_FP32_MFMA_TFLOPS, "fp32mfma", k32, 1.0), "f32"
     elif args.fp16_act:
-        wall_ms, kern_ms, info = timed(rinr.FLAG_FP16_ACT)
-        roof, dtype_name = alu_roofline(kern_ms, alu_ops16, "xdl16", k16), "f16 activations, f32 accumulate"
+        t = timed(F16A)
+        roof, dtype_name = roofline(t, PEAK_FP16_MFMA_TFLOPS, "xdl16", k16, fx / 2), "f16 activations, f32 accumulate"
     elif args.fp16_all:
-        wall_ms, kern_ms, info = timed(rinr.FLAG_FP16_ALL)
-        roof, dtype_name = alu_roofline(kern_ms, alu_ops16a, "xdl16all", k16a), "f16 weights and activations, f32 accumulate"
+        t = timed(F16W)
+        roof, dtype_name = roofline(t, PEAK_FP16_MFMA_TFLOPS, "xdl16all", k16a, 1.0), "f16 weights and activations, f32 accumulate"
     else:
-        wall_ms, kern_ms, info = timed(0)
-        roof = alu_roofline(kern_ms, alu_ops, "xdl", "decode_xdl_kernel (fp16 hi+lo operands on MFMA, fp32 accumulate)")
+        t = timed(0)
+        roof = roofline(t, PEAK_FP16_MFMA_TFLOPS, "xdl", kx, fx)
         dtype_name = "f16x2-split operands, f32 accumulate"
-        w2, k2, i2 = timed(rinr.FLAG_FP32_MFMA)
-        alt = {"mode": "RINR_FLAG_FP32_MFMA", "value": pixels / (w2 * 1e-3), "unit": "pixels/s", "ms_per_step": w2,
-               "roofline": mfma_roofline(k2, "fp32mfma"), "launch": i2}
-        w3, k3, i3 = timed(rinr.FLAG_FP16_ACT)
-        alt16 = {"mode": "RINR_FLAG_FP16_ACT (opt-in, reduced precision: one fp16 value per hidden activation)",
-                 "value": pixels / (w3 * 1e-3), "unit": "pixels/s", "ms_per_step": w3,
-                 "roofline": alu_roofline(k3, alu_ops16, "xdl16", k16), "launch": i3}
-        w4, k4, i4 = timed(rinr.FLAG_FP16_ALL)
-        alt16a = {"mode": "RINR_FLAG_FP16_ALL (opt-in, reduced precision: fp16 weights and activations in the hidden layers)",
-                  "value": pixels / (w4 * 1e-3), "unit": "pixels/s", "ms_per_step": w4,
-                  "roofline": alu_roofline(k4, alu_ops16a, "xdl16all", k16a), "launch": i4}
+        t2 = timed(rinr.FLAG_FP32_MFMA)
+        alt = mode_entry("RINR_FLAG_FP32_MFMA", t2, roofline(t2, PEAK_FP32_MFMA_TFLOPS, "fp32mfma", k32, 1.0))
+        t3 = timed(F16A)
+        alt16 = mode_entry("RINR_FLAG_FP16_ACT | RINR_FLAG_FP16_UNCHECKED (reduced precision, forced past its worst-case bound: "
+                           "one fp16 value per hidden activation)", t3, roofline(t3, PEAK_FP16_MFMA_TFLOPS, "xdl16", k16, fx / 2))
+        t4 = timed(F16W)
+        alt16a = mode_entry("RINR_FLAG_FP16_ALL | RINR_FLAG_FP16_UNCHECKED (reduced precision, forced past its worst-case bound: "
+                            "fp16 weights and activations in the hidden layers)", t4, roofline(t4, PEAK_FP16_MFMA_TFLOPS, "xdl16all", k16a, 1.0))
+    wall_ms, kern_ms, info = t[0], t[1], t[4]
     assert st.status() == 0
+    bounds = st.error_bounds()
 
     res = {
         "metric": "decoded pixels/sec (and images/sec) on 1 MI355X; % of MFMA/VALU FLOP peak",
@@ -281,7 +300,9 @@ def main() -> int:
         "config": {"workload": w.name, "images": n, "H": H, "W": W,
                    "outputs": "fp32+uint8 NCHW" if (w.out_u8 and not args.augment) else "fp32 NCHW",
                    "augmentation": "per-slot affine grid map + per-channel normalisation" if args.augment else "none",
-                   "flop_per_pixel_mean": float(flop_px.mean()), "alu_ops_per_pixel_mean": float(alu_px.mean()),
+                   "flop_per_pixel_mean": float(flop_px.mean()), "sines_per_pixel_mean": sines / pixels,
+                   "kept_weight_fraction": nz_flops / flops,
+                   "reduced_precision_error_bounds": {"fp16_act": bounds[0], "fp16_all": bounds[1], "granted_below": 9.5e-4},
                    "launch": info},
         "roofline": roof,
     }
@@ -296,13 +317,19 @@ def main() -> int:
         from oracle import oracle
         cores = host_threads()
         per_img_s = float(flop_px.mean()) * H * W / 2.0e9        # the scalar fp64 oracle runs near 2 GFLOP/s per core
-        n_s = int(max(1, min(n, round(15.0 * cores / max(per_img_s, 1e-4)))))   # about 15 s of wall time
+        n_s = int(max(1, min(n, round(12.0 * cores / max(per_img_s, 1e-4)))))   # about 12 s of wall time
         sample = w.image_ids[:n_s]
         tc = time.perf_counter()
         oracle.decode(w.models, sample, H, W, w.w0, w.coord_lo, w.coord_hi, want_u8=w.out_u8, n_threads=cores)
         dt = time.perf_counter() - tc
+        n_1 = int(max(1, min(n, round(5.0 / max(per_img_s, 1e-4)))))             # about 5 s on one core
+        tc = time.perf_counter()
+        oracle.decode(w.models, w.image_ids[:n_1], H, W, w.w0, w.coord_lo, w.coord_hi, want_u8=w.out_u8, n_threads=1)
+        dt1 = time.perf_counter() - tc
         res["cpu_baseline"] = {"value": n_s * H * W / dt, "unit": "pixels/s", "cores": cores, "kind": "oracle",
-                               "sample": f"first {n_s} of {n} slots, all pixels, fp64 C oracle with OpenMP over images, {dt:.1f} s"}
+                               "sample": f"first {n_s} of {n} slots, all pixels, fp64 C oracle with OpenMP over images, {dt:.1f} s",
+                               "single_core": {"value": n_1 * H * W / dt1, "unit": "pixels/s", "cores": 1,
+                                               "sample": f"first {n_1} of {n} slots, all pixels, one thread, {dt1:.1f} s"}}
     st.close()
     print(json.dumps(res))
     return 0

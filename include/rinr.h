@@ -103,20 +103,42 @@ int rinr_unpack_layer(const void *host_blob, size_t bytes, int64_t model, int32_
 /* ---- device-resident store ------------------------------------------------------ */
 typedef struct rinr_store rinr_store;
 
-/* Opens a store over a blob already resident in device memory (device_blob, 16-byte
- * aligned, `bytes` long).  host_blob, if not NULL, is a host copy of the same bytes and
- * is validated in full (header, index, every record's offsets and sizes) without
- * touching the device; if NULL the blob is copied back from the device once, here, for
- * the same validation.  The store neither copies nor owns the blob: it must stay
- * allocated and unchanged until rinr_store_close.  Must be called with the blob's
- * device current.  Allocates the handle and an 8-byte device status word.
- * RINR_E_UNSUPPORTED: some model's expanded weights fit the 160 KB of LDS in neither kernel
- * form (fp32: 4 bytes per padded weight; split precision: 2 bytes for 2..8-bit layers, 4
- * otherwise).  A store that fits only the split-precision form opens, and decodes that ask
- * for RINR_FLAG_FP32_MFMA return RINR_E_UNSUPPORTED. */
+/* Options of rinr_store_open_ex.  NULL, or a zero in a field, means the default. */
+typedef struct {
+    int32_t fp32_tile_rows;  /* MFMA tile of the fp32 kernels at padded widths 32 and 64: 32 (32x32x2, default)
+                                or 16 (16x16x4).  Fixes the kernels' on-chip weight layout for this store. */
+    int32_t lds_budget;      /* on-chip memory a workgroup may use, in bytes: a multiple of 16 from 20480 to 163840
+                                (default: all 160 KB).  Models that do not fit it are decoded with their layers
+                                streamed in groups; a small budget forces that on small models (tests).        */
+} rinr_open_opts;
+
+/* Sec. III-B: the whole dataset is moved to GPU memory once, in weight form, before training starts;
+ * every batch is then selected and decoded from that resident copy.  rinr_store_open makes the resident
+ * copy usable: it opens a store over a blob already in device memory (device_blob, 16-byte aligned,
+ * `bytes` long).  host_blob, if not NULL, is a host copy of the same bytes and is validated in full
+ * (header, index, every record's offsets and sizes) without touching the device; if NULL the blob is
+ * copied back from the device once, here, for the same validation.  The store neither copies nor owns
+ * the blob: it must stay allocated and unchanged until rinr_store_close.  Must be called with the
+ * blob's device current.  Allocates the handle and an 8-byte device status word.
+ * Every store that rinr_pack writes opens: models whose expanded weights fit the 160 KB of on-chip memory
+ * are decoded from a resident copy of the whole model, deeper ones with their layers streamed through it
+ * in groups (slower per pixel, same results).
+ * rinr_store_open == rinr_store_open_ex with opts = NULL. */
 int rinr_store_open(const void *device_blob, const void *host_blob, size_t bytes, rinr_store **store);
+int rinr_store_open_ex(const void *device_blob, const void *host_blob, size_t bytes, const rinr_open_opts *opts,
+                       rinr_store **store);
+/* Frees the handle and its status word (Sec. III-B: the resident dataset is released by its owner, the
+ * caller; the blob itself is untouched).  No decode of this store may still be running. */
 int rinr_store_close(rinr_store *store);
+/* Size of the resident dataset (Sec. III-A: one model per image): number of models, widest hidden layer,
+ * most linear layers.  Any output pointer may be NULL. */
 int rinr_store_info(const rinr_store *store, int64_t *n_models, int32_t *max_width, int32_t *max_layers);
+/* Worst-case output error (absolute, before any normalisation) that the reduced-precision modes can cause
+ * on this store, from its own weights: bounds[0] for RINR_FLAG_FP16_ACT, bounds[1] for RINR_FLAG_FP16_ALL.
+ * With |sin'| <= 1, u = 2^-12 and R_l the largest absolute row sum of layer l:
+ * d_0 = u, d_l = w0 R_l (d_{l-1} + t) + u, bound = R_out d_last  (t = 2^-11 for fp16 weights, else 0).
+ * A mode is used only where its bound is at most 9.5e-4 (see the flags). */
+int rinr_store_error_bounds(const rinr_store *store, float bounds[2]);
 
 /* ---- decode ------------------------------------------------------------------------ */
 enum { RINR_OUT_F32 = 1,           /* out: float [n][3][H][W], clamp(y, 0, 1)                 */
@@ -131,18 +153,24 @@ enum { RINR_FLAG_NO_CLAMP = 1,     /* fp32 output only: write the linear output 
        RINR_FLAG_FP16_ACT = 8,     /* faster, less precise: activations travel between layers as one
                                       fp16 value (relative rounding 2^-12 each) instead of a hi+lo
                                       pair; weights, coordinates and accumulation as in the default
-                                      kernel.  Measured max-abs error against the fp64 definition:
-                                      2e-5 .. 5e-5 on the benchmark workloads, up to 5.5e-4 on the
-                                      test models, 1e-3 on a fitted 10-layer model of width 40 (a
-                                      quarter of an 8-bit step); it grows with depth and with the output layer's
-                                      gain and has no model-independent bound.  Ignored together
-                                      with RINR_FLAG_FP32_MFMA, and where the store is served by the
-                                      fp32 kernels anyway (operands beyond fp16 range)            */
-       RINR_FLAG_FP16_ALL = 16 };  /* fastest, least precise: RINR_FLAG_FP16_ACT, and the hidden layers'
+                                      kernel.  Honoured only on stores whose a-priori error bound
+                                      (rinr_store_error_bounds) is at most 9.5e-4, so that the result stays
+                                      within 1e-3 of the fp64 definition; other stores are decoded by the
+                                      default kernel.  Ignored together with RINR_FLAG_FP32_MFMA, and where
+                                      the store is served by the fp32 kernels anyway (operands beyond fp16
+                                      range)                                                            */
+       RINR_FLAG_FP16_ALL = 16,    /* fastest, least precise: RINR_FLAG_FP16_ACT, and the hidden layers'
                                       weights are rounded to fp16 as well (after dequantisation and the
                                       w0 scaling): fp16 operands with fp32 accumulation throughout the
                                       hidden layers; the first and the last layer keep their hi+lo
-                                      pairs.  About 1.4 times the error of RINR_FLAG_FP16_ACT.          */
+                                      pairs.  Honoured under the same rule with its own bound; a store that
+                                      passes only the RINR_FLAG_FP16_ACT bound is decoded in that mode.     */
+       RINR_FLAG_FP16_UNCHECKED = 32 };
+                                   /* with one of the two flags above: use the mode whatever the bound says.
+                                      The bound is a worst case that grows with the product of the layers'
+                                      gains; measured errors of deep models are far below it (2e-5 .. 8e-5 on
+                                      the benchmark workloads) but nothing guarantees them: the caller
+                                      takes the responsibility.                                            */
 
 /* Augmentation on the GPU, fused into the decode (Sec. III-B: decoded images are augmented
  * on the GPU before they reach the backbone).  Geometric augmentation (flip, crop + resize,
@@ -164,6 +192,12 @@ typedef struct {
                                 results are the same bytes.  Calls that may overlap need their own.
                                 The ordering kernel is one workgroup: about 6 us per thousand slots.   */
     size_t workspace_bytes;  /* >= rinr_decode_workspace_bytes(n), else RINR_E_SIZE                    */
+    /* Launch shape, for experiments and tests; 0 = chosen by the library (what the benchmarks use).     */
+    int32_t launch_threads;        /* threads per workgroup: a multiple of 64 up to 768                  */
+    int32_t launch_blocks_per_cu;  /* fixed grid target in workgroups per compute unit (1..1024) instead of
+                                      the built-in cost model's split of each slot's pixels              */
+    int32_t one_grid_min_tiles;    /* stores that mix width classes decode images of at least this many
+                                      64-pixel tiles in one grid, smaller ones class by class (default 64) */
 } rinr_decode_opts;
 
 /* Bytes of rinr_decode_opts.workspace a batch of n slots needs (4 per slot). */
@@ -185,41 +219,42 @@ size_t rinr_decode_workspace_bytes(int32_t n);
  * range; sine networks stay within a few tens of radians).  The default split-precision
  * kernels also need |w * w0/2pi| and the coordinate bounds below 6e4 (fp16 range); a store
  * that breaks this is served by the fp32 MFMA kernels automatically.
- * A store keeps the launch plan of its last decode: use one store from one host thread at a time.
+ * The handle is not const: a store keeps the launch plan and the launch record of its last decode, so one
+ * store is used from one host thread at a time (different stores are independent).
  * rinr_decode_batch == rinr_decode_batch_ex with {RINR_OUT_F32, 0, NULL, NULL} and no workspace. */
-int rinr_decode_batch(const rinr_store *models, const int64_t *image_ids, int32_t n,
+int rinr_decode_batch(rinr_store *models, const int64_t *image_ids, int32_t n,
                       int32_t H, int32_t W, void *out, void *stream);
-int rinr_decode_batch_ex(const rinr_store *models, const int64_t *image_ids, int32_t n,
+int rinr_decode_batch_ex(rinr_store *models, const int64_t *image_ids, int32_t n,
                          int32_t H, int32_t W, void *out, const rinr_decode_opts *opts, void *stream);
 
-/* Synchronises `stream`, then reads (and leaves set) the count of out-of-range image
- * ids seen by decodes on this store so far. */
+/* Sec. III-B selects the batch on the GPU with no CPU in the loop, so an id outside the dataset can only
+ * be seen by the kernel: this call synchronises `stream`, then reads (and leaves set) the count of
+ * out-of-range image ids seen by decodes on this store so far. */
 int rinr_store_status(const rinr_store *store, int64_t *bad_id_count, void *stream);
 
-/* Test hook for the expand/dequantise stage: runs the same device routine the decode
- * kernels use to rebuild layer `layer` of model `id` from the packed record (mask,
- * kept-code stream, affine map), reading the result back out of the kernel's on-chip
- * layout, and writes float[out*in] (row-major [out][in], 0 where pruned) to device_out
- * and, if bias_out is not NULL, float[out] biases.  No sine pre-scaling is applied, so
- * the values are bit-comparable with scale * (code - zp) rounded once to fp32. */
+/* Test hooks for the expand/dequantise stage (Sec. IV-A mask, Sec. IV-B codes).  They cite no passage of their
+ * own: they expose, for bit-exact checks, what the decode kernels hold on chip after running the same device
+ * routine the decode uses to rebuild layer `layer` of model `id` from the packed record.  No sine pre-scaling
+ * is applied.  Outputs are device pointers, row-major [out][in], 0 where pruned; bias_out (float[out]) may be NULL.
+ * rinr_debug_dequant: the fp32 kernels' layout; the values are bit-comparable with scale * (code - zp) rounded
+ * once to fp32.
+ * rinr_debug_dequant_split: the split-precision kernels' fp16 operand blocks.  For a 2..8-bit hidden layer hi_out
+ * is the integer code - zp the matrix cores multiply by, lo_out is 0 and *scale_out the multiplier applied to
+ * the accumulator; for every other layer hi_out = fp16(w) and lo_out = fp16(w - hi) as floats and *scale_out = 1.
+ * The first layer's operand block holds its weights several times (once per pixel tile and operand slot): an
+ * entry whose copies disagree is written as NaN.  bias_out receives what the bias tile holds (bias / scale for
+ * a 2..8-bit hidden layer).  fp16_weights != 0 exports the RINR_FLAG_FP16_ALL form: hi_out = fp16(w). */
 int rinr_debug_dequant(const rinr_store *store, int64_t id, int32_t layer, float *device_out,
                        float *bias_out, void *stream);
+int rinr_debug_dequant_split(const rinr_store *store, int64_t id, int32_t layer, int32_t fp16_weights, float *hi_out,
+                             float *lo_out, float *bias_out, float *scale_out, void *stream);
 
 /* Grid the last decode on this store used (diagnostics / benchmarks):
  * info[0] = kernel launches, info[1] = workgroups, info[2] = threads per workgroup,
- * info[3] = dynamic LDS bytes per workgroup. */
-int rinr_last_launch_info(const rinr_store *store, int32_t info[4]);
-
-/* Process-wide tuning knobs for experiments; defaults are what the benchmarks use.
- * knob 0: MFMA tile rows for padded widths 32 and 64: 32 (32x32x2 fp32, default) or 16
- *         (16x16x4 fp32); read at rinr_store_open.
- * knob 1: 0 = split each slot's pixels over workgroups by the built-in cost model; else a
- *         fixed grid target in workgroups per compute unit (1..1024).
- * knob 2: threads per workgroup: 0 = by image size, or a multiple of 64 up to 768.
- * knob 3: 1 = use the fp32 MFMA kernels for every decode (as RINR_FLAG_FP32_MFMA).
- * knob 4: stores that mix width classes decode images of at least this many 64-pixel tiles in one grid, smaller ones
- *         class by class (default 64). */
-int rinr_tune(int knob, int value);
+ * info[3] = dynamic LDS bytes per workgroup, info[4] = kernels that ran: 0 split precision (default),
+ * 1 fp32 MFMA, 2 fp16 activations, 3 fp16 weights and activations, info[5] = 1 if the layers were streamed
+ * through on-chip memory in groups (a model too deep to be resident), else 0. */
+int rinr_last_launch_info(const rinr_store *store, int32_t info[6]);
 
 const char *rinr_strerror(int code);
 /* hipError_t of the last failed HIP call on this thread (0 if none), as an int. */

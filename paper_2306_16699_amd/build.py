@@ -15,7 +15,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "
 
 
 def build(verbose: bool = False, extra=()) -> str:
-    srcs = [os.path.join(CSRC, n) for n in ("rinr_api.hip", "rinr_pack.cpp", "rinr_fit.hip", "rinr_encode.cpp")]
+    srcs = [os.path.join(CSRC, n) for n in ("rinr_api.hip", "rinr_pack.cpp", "rinr_bounds.cpp", "rinr_fit.hip", "rinr_encode.cpp")]
     cmd = ["hipcc", *HIP_FLAGS, *extra, "-o", SO, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -116,15 +116,16 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
 }
 
 // The weights of a model are cut into blocks of 64 consecutive flat indices, layer after layer, and the workgroup's
-// wavefronts share the blocks of the whole model evenly: wavefront w of nw takes blocks [B w / nw, B (w + 1) / nw) of
-// the B blocks counted over all layers, so a wavefront touches one or two layers whatever the depth and the widths.
+// wavefronts share the blocks of the layers at hand (the whole model, or one group of its layers) evenly: wavefront w
+// of nw takes blocks [B w / nw, B (w + 1) / nw) of the B blocks counted over those layers, so a wavefront touches one
+// or two layers whatever the depth and the widths.
 struct ExpandShare {
     uint32_t g0, g1;      // this wavefront's range of blocks, counted over all layers
     uint32_t base;        // blocks of the layers before the one at hand (advanced by expand_layer)
 };
-__device__ __forceinline__ ExpandShare expand_share(const uint32_t *rec, int L, int wave, int nwaves) {
+__device__ __forceinline__ ExpandShare expand_share(const uint32_t *rec, int l0, int l1, int wave, int nwaves) {
     uint32_t total = 0;
-    for (int l = 0; l < L; ++l) {
+    for (int l = l0; l < l1; ++l) {
         const LayerRec *r = (const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
         total += ((uint32_t)r->n_in * r->n_out + 63) >> 6;
     }
@@ -135,7 +136,8 @@ __device__ __forceinline__ ExpandShare expand_share(const uint32_t *rec, int L, 
     return s;
 }
 
-// This wavefront's part of one layer, one weight per lane.  `rec` is the model record (words, in LDS).  Over the
+// This wavefront's part of one layer, one weight per lane.  `rec` is the model record (words; the staged copy in LDS,
+// or the record itself in global memory).  Over the
 // workgroup, put(o, i, w, q) receives every weight of the true n_out x n_in matrix exactly once: w the fp32 value
 // (0.0f where pruned) and q the integer code - zp of a coded layer (0 where pruned or for fp32 layers); putb(o, b)
 // every bias (from the wavefront that holds the layer's first block).  A kept weight's code is found by its rank
@@ -199,7 +201,7 @@ __device__ __forceinline__ void expand_model(float *lds, const uint32_t *rec, in
     for (int q = tid; q < total; q += nthreads) lds[q] = 0.0f;
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, nwaves = nthreads >> 6;
-    ExpandShare sh = expand_share(rec, L, wave, nwaves);
+    ExpandShare sh = expand_share(rec, 0, L, wave, nwaves);
     for (int l = 0; l < L; ++l) {
         const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
         if (l == L - 1) {
@@ -219,6 +221,31 @@ __device__ __forceinline__ void expand_model(float *lds, const uint32_t *rec, in
     __syncthreads();
 }
 
+// ---- which models are decoded from a resident copy -----------------------------------------------
+// A model is resident when its expanded weights and the staged copy of its packed record fit the LDS of one
+// workgroup together; the host (launch sizes) and the kernels (which workgroups a launch serves) use this one rule.
+constexpr uint32_t kLdsLimit = 160 * 1024;   // LDS per workgroup on gfx950
+enum { kFitFp32 = 0,        // fp32 kernels: 4 bytes per padded weight
+       kFitXdlOne = 1,      // split-precision kernels, one fp16 block per hidden layer (2..8-bit layers, or fp16 weights)
+       kFitXdlTwo = 2 };    // ... two blocks per hidden layer (a store with fp32 or 16-bit hidden layers)
+__host__ __device__ inline uint32_t fp32_model_bytes(uint32_t cls, uint32_t tile_rows_wide, uint32_t L) {
+    const uint32_t wp = 16u * cls, tm = (cls == 2 || cls == 4) ? tile_rows_wide : 16u, g = 64u / tm;
+    const uint32_t mt = wp / tm, mts = mt == 3 ? 4u : mt, ksteps = wp / g;
+    const uint32_t first = 64u * mts, hidden = ksteps * 64u * mts;
+    return 4u * (first + (L - 1) * wp + (L - 2) * hidden + 4u * wp + 4u);
+}
+__host__ __device__ inline uint32_t xdl_model_bytes(int cls, int n_layers, int n_int, int n_raw);
+__host__ __device__ inline uint32_t resident_bytes(uint32_t form, uint32_t cls, uint32_t L, uint32_t tile_rows_wide) {
+    const uint32_t b = form == kFitFp32 ? fp32_model_bytes(cls, tile_rows_wide, L)
+                                        : xdl_model_bytes((int)cls, (int)L, form == kFitXdlOne ? (int)L - 2 : 0,
+                                                          form == kFitXdlTwo ? (int)L - 2 : 0);
+    return (b + 15u) & ~15u;
+}
+__host__ __device__ inline bool resident_fits(uint32_t form, uint32_t cls, uint32_t L, uint32_t rec_bytes, uint32_t tile_rows_wide,
+                                              uint32_t budget) {
+    return (uint64_t)resident_bytes(form, cls, L, tile_rows_wide) + rec_bytes <= budget;
+}
+
 // ---- decode kernel ---------------------------------------------------------------------------
 struct DecodeArgs {
     const uint8_t *blob;
@@ -234,8 +261,14 @@ struct DecodeArgs {
     float pre;                    // w0 / (2 pi)
     uint32_t chunks;              // workgroups per slot
     uint32_t tiles_per_chunk;     // 64-pixel tiles per workgroup
-    uint32_t stage_off[5];        // per width class: float offset of the record staging area in LDS
+    uint32_t lds_bytes;           // dynamic LDS of this launch; a resident model's packed record is staged at its end
     uint32_t cls;                 // width class this launch serves (padded width / 16); 0 = every class
+    uint32_t stream_mode;         // 0: every model of the store is decoded from a resident expanded copy;
+                                  // 1: this launch skips the models too deep for that; 2: this launch decodes only those,
+                                  //    streaming their layers through LDS in groups
+    uint32_t fit_form;            // how a model's resident size is reckoned (resident_fits)
+    uint32_t tile_rows_wide;      // MFMA tile rows of the fp32 kernels at padded widths 32 and 64
+    uint32_t lds_budget;          // LDS a workgroup may use (160 KB unless the store was opened with less)
     uint32_t no_clamp;
     uint32_t handle_bad;          // this launch zero-fills and counts out-of-range ids
     float neg1;                   // -1.0f, passed as data (keeps a subtraction in mixed-precision fma form)
@@ -312,7 +345,7 @@ __global__ __launch_bounds__(1024) void order_slots_kernel(const uint8_t *blob, 
 // ---- gather: workgroup -> (slot, tile range); slot -> id -> index entry (Sec. III-B batch select).
 // Returns false when the workgroup has nothing to decode: empty tile range, or an out-of-range id
 // (then the launch that handles bad ids has zero-filled the range and counted it), or a model of
-// another class than this launch serves.
+// another class, or of the other kind (resident / streamed), than this launch serves.
 __device__ __forceinline__ bool decode_prologue(const DecodeArgs &a, Work &w) {
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const uint32_t turn = blockIdx.x / a.chunks;
@@ -337,50 +370,27 @@ __device__ __forceinline__ bool decode_prologue(const DecodeArgs &a, Work &w) {
     }
     w.e = *(const IndexEntry *)(a.blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
     w.cls = w.e.width == 0 ? 1u : (w.e.width + 15u) >> 4;
-    return a.cls == 0 || w.cls == a.cls;
+    if (a.cls != 0 && w.cls != a.cls) return false;
+    if (a.stream_mode) {
+        const bool fits = resident_fits(a.fit_form, w.cls, w.e.n_layers, w.e.nbytes, a.tile_rows_wide, a.lds_budget);
+        if (fits != (a.stream_mode == 1u)) return false;
+    }
+    return true;
 }
 
-template <int TM, int WP>
-__device__ __forceinline__ void decode_body(const DecodeArgs &a, const Work &w, float *lds) {
+// ---- the layers of the fp32 kernel, on one wavefront's 64-pixel tile ------------------------------------
+// Activations live in Bv[pixel tile][k-step] between layers: the accumulator registers of one layer are the B
+// operands of the next.  The weight pointers are per lane (lane * MTS added by the caller), bias tiles per group.
+template <int TM, int WP> struct Fp32Tile {
     typedef Layout<TM, WP> LY;
     typedef Tile<TM> T;
     typedef typename T::acc_t acc_t;
-    constexpr int G = LY::G, RV = LY::RV, MT = LY::MT, MTS = LY::MTS, KSTEPS = LY::KSTEPS;
-    constexpr int NT = G;                      // pixel tiles per wavefront: NT * TM = 64 pixels
-    const int tid = threadIdx.x, nthreads = blockDim.x;
-    const uint32_t slot = w.slot, tile0 = w.tile0, tile1 = w.tile1;
-    const size_t plane0 = w.plane0;
-    const IndexEntry e = w.e;
-    const int L = e.n_layers;
+    static constexpr int G = LY::G, RV = LY::RV, MT = LY::MT, MTS = LY::MTS, KSTEPS = LY::KSTEPS;
+    static constexpr int NT = G;               // pixel tiles per wavefront: NT * TM = 64 pixels
 
-    // ---- stage the packed record, expand it
-    uint32_t *stage = (uint32_t *)(lds + a.stage_off[WP / 16]);
-    {
-        const uint4 *src = (const uint4 *)(a.blob + e.off);
-        uint4 *dst = (uint4 *)stage;
-        for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
-    }
-    expand_model<TM, WP>(lds, stage, L, a.pre, tid, nthreads);   // zero-fill barrier orders the staging too
-    // Tiles are handed out through a counter in LDS (the first word of the staging area, dead by
-    // now): wavefronts sharing a SIMD do not progress at the same rate.
-    uint32_t *next_tile = stage;
-    if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
-    __syncthreads();
-
-    const int lane = tid & 63, wave = tid >> 6;
-    const int g = lane / TM;
-    const float *wfirst = lds + LY::off_first() + lane * MTS;
-    const float *wout = lds + LY::off_out(L) + g * KSTEPS * 4;
-    const float ob0 = lds[LY::off_outb(L) + 0], ob1 = lds[LY::off_outb(L) + 1], ob2 = lds[LY::off_outb(L) + 2];
-    float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
-    if (a.affine)
-        for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)slot * 6 + q];
-
-    for (uint32_t tile = tile0 + wave; tile < tile1;) {
-        float Bv[NT][KSTEPS];
-        acc_t D[NT][MT];
-        // ---- coordinates of this lane's pixel in each of its NT tiles; lane group 0 feeds x, 1 feeds y
-        float bx[NT];
+    // coordinates of this lane's pixel in each of its NT tiles; lane group 0 feeds x, 1 feeds y
+    static __device__ __forceinline__ void coords(const DecodeArgs &a, const float (&af)[6], uint32_t tile, int lane, float (&bx)[NT]) {
+        const int g = lane / TM;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             uint32_t p = (tile << 6) + nt * TM + (lane % TM);
@@ -391,59 +401,62 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const Work &w, 
             const float xa = fmaf(af[0], x, fmaf(af[1], y, af[2])), ya = fmaf(af[3], x, fmaf(af[4], y, af[5]));
             bx[nt] = g == 0 ? xa : (g == 1 ? ya : 0.0f);
         }
-        // ---- first layer 2 -> width: one k-step, bias as the C operand
-        {
-            float a0[MT];
+    }
+    // first layer 2 -> width: one k-step, bias as the C operand, then the sine
+    static __device__ __forceinline__ void first(float (&Bv)[NT][KSTEPS], const float *wfirst, const float *bt, const float (&bx)[NT]) {
+        acc_t D[NT][MT];
+        float a0[MT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a0[mt] = wfirst[mt];
-            const float *bt = lds + LY::off_bias(0) + g * RV;
+        for (int mt = 0; mt < MT; ++mt) a0[mt] = wfirst[mt];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            acc_t c;
+#pragma unroll
+            for (int v = 0; v < RV; ++v) c[v] = bt[mt * G * RV + v];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(a0[mt], bx[nt], c);
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < RV; ++v) Bv[nt][mt * RV + v] = sin_rev(D[nt][mt][v]);
+    }
+    // hidden layer width -> width
+    static __device__ __forceinline__ void hidden(float (&Bv)[NT][KSTEPS], const float *wl, const float *bt) {
+        acc_t D[NT][MT];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            float av[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) av[mt] = wl[s * 64 * MTS + mt];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                acc_t c;
+                if (s == 0) {
+                    acc_t c;
 #pragma unroll
-                for (int v = 0; v < RV; ++v) c[v] = bt[mt * G * RV + v];
+                    for (int v = 0; v < RV; ++v) c[v] = bt[mt * G * RV + v];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(a0[mt], bx[nt], c);
-            }
+                    for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(av[mt], Bv[nt][0], c);
+                } else {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int v = 0; v < RV; ++v) Bv[nt][mt * RV + v] = sin_rev(D[nt][mt][v]);
-        }
-        // ---- hidden layers width -> width
-        for (int l = 1; l < L - 1; ++l) {
-            const float *wl = lds + LY::off_hidden(L, l) + lane * MTS;
-            const float *bt = lds + LY::off_bias(l) + g * RV;
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                float av[MT];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) av[mt] = wl[s * 64 * MTS + mt];
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    if (s == 0) {
-                        acc_t c;
-#pragma unroll
-                        for (int v = 0; v < RV; ++v) c[v] = bt[mt * G * RV + v];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(av[mt], Bv[nt][0], c);
-                    } else {
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(av[mt], Bv[nt][s], D[nt][mt]);
-                    }
+                    for (int nt = 0; nt < NT; ++nt) D[nt][mt] = T::mfma(av[mt], Bv[nt][s], D[nt][mt]);
                 }
             }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int v = 0; v < RV; ++v) Bv[nt][mt * RV + v] = sin_rev(D[nt][mt][v]);
         }
-        // ---- output layer width -> 3 on the vector ALU: each lane sums over the rows it owns,
-        //      then the G lane groups are added together
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int v = 0; v < RV; ++v) Bv[nt][mt * RV + v] = sin_rev(D[nt][mt][v]);
+    }
+    // output layer width -> 3 on the vector ALU (each lane sums over the rows it owns, then the G lane groups are
+    // added together), clamp, optional normalisation, NCHW store: lane <-> pixel tile * 64 + lane
+    static __device__ __forceinline__ void output(const DecodeArgs &a, const float (&Bv)[NT][KSTEPS], const float *wout, float ob0,
+                                                  float ob1, float ob2, uint32_t tile, int lane, size_t plane0) {
+        const int g = lane / TM;
         float o[NT][3];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) o[nt][0] = o[nt][1] = o[nt][2] = 0.0f;
@@ -463,7 +476,6 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const Work &w, 
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                 for (int c = 0; c < 3; ++c) o[nt][c] += __shfl_xor(o[nt][c], d, 64);
-        // lane group g stores pixel tile g: lane <-> pixel tile*64 + lane
         float r0 = o[0][0], r1 = o[0][1], r2 = o[0][2];
 #pragma unroll
         for (int nt = 1; nt < NT; ++nt)
@@ -492,9 +504,125 @@ __device__ __forceinline__ void decode_body(const DecodeArgs &a, const Work &w, 
                 dst[2 * (size_t)a.HW] = (uint8_t)rintf(255.0f * r2);
             }
         }
+    }
+};
+
+// Resident form: the whole model is expanded once per workgroup and every tile runs through all layers.
+template <int TM, int WP>
+__device__ __forceinline__ void decode_body(const DecodeArgs &a, const Work &w, float *lds) {
+    typedef Layout<TM, WP> LY;
+    typedef Fp32Tile<TM, WP> FT;
+    constexpr int RV = LY::RV, MTS = LY::MTS, KSTEPS = LY::KSTEPS, NT = FT::NT;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const uint32_t slot = w.slot, tile0 = w.tile0, tile1 = w.tile1;
+    const size_t plane0 = w.plane0;
+    const IndexEntry e = w.e;
+    const int L = e.n_layers;
+
+    // ---- stage the packed record at the end of the workgroup's LDS, expand it at the start
+    uint32_t *stage = (uint32_t *)((char *)lds + (a.lds_bytes - e.nbytes));
+    {
+        const uint4 *src = (const uint4 *)(a.blob + e.off);
+        uint4 *dst = (uint4 *)stage;
+        for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
+    }
+    expand_model<TM, WP>(lds, stage, L, a.pre, tid, nthreads);   // zero-fill barrier orders the staging too
+    // Tiles are handed out through a counter in LDS (the first word of the staging area, dead by
+    // now): wavefronts sharing a SIMD do not progress at the same rate.
+    uint32_t *next_tile = stage;
+    if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int g = lane / TM;
+    const float *wfirst = lds + LY::off_first() + lane * MTS;
+    const float *wout = lds + LY::off_out(L) + g * KSTEPS * 4;
+    const float ob0 = lds[LY::off_outb(L) + 0], ob1 = lds[LY::off_outb(L) + 1], ob2 = lds[LY::off_outb(L) + 2];
+    float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
+    if (a.affine)
+        for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)slot * 6 + q];
+
+    for (uint32_t tile = tile0 + wave; tile < tile1;) {
+        float Bv[NT][KSTEPS];
+        float bx[NT];
+        FT::coords(a, af, tile, lane, bx);
+        FT::first(Bv, wfirst, lds + LY::off_bias(0) + g * RV, bx);
+        for (int l = 1; l < L - 1; ++l)
+            FT::hidden(Bv, lds + LY::off_hidden(L, l) + lane * MTS, lds + LY::off_bias(l) + g * RV);
+        FT::output(a, Bv, wout, ob0, ob1, ob2, tile, lane, plane0);
         uint32_t nt_ = 0;
         if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
         tile = __builtin_amdgcn_readfirstlane(nt_);
+    }
+}
+
+// One layer into a slot of the streamed layout: the layer's weights in the resident layout's order at the slot's
+// start, its bias tile HIDDEN floats in (the first and the output layer use less of the slot).
+template <int TM, int WP>
+__device__ __forceinline__ void expand_slot(float *wb, const uint32_t *rec, int L, int l, float pre, int lane, ExpandShare &sh) {
+    typedef Layout<TM, WP> LY;
+    const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
+    float *bb = wb + LY::HIDDEN;
+    if (l == L - 1)
+        expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { wb[LY::idx_out(o, i)] = v; },
+                     [=](int o, float v) { bb[o] = v; });
+    else if (l == 0)
+        expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { wb[LY::idx_first(o, i)] = v * pre; },
+                     [=](int o, float v) { bb[LY::idx_bias(o)] = v * pre; });
+    else
+        expand_layer(rec, r, lane, sh, [=](int o, int i, float v, int) { wb[LY::idx_hidden(o, i)] = v * pre; },
+                     [=](int o, float v) { bb[LY::idx_bias(o)] = v * pre; });
+}
+
+// Streamed form, for a model whose expanded weights do not fit LDS: the layers go through LDS in groups of as many
+// as fit.  Every wavefront holds one tile's activations in registers; for each group the workgroup expands the
+// group's layers straight from the packed record in global memory, then every wavefront takes its tile through
+// them.  A slot is one layer's weights followed by its bias tile (the first and the output layer use less of it).
+template <int TM, int WP>
+__device__ __forceinline__ void decode_stream_body(const DecodeArgs &a, const Work &w, float *lds) {
+    typedef Layout<TM, WP> LY;
+    typedef Fp32Tile<TM, WP> FT;
+    constexpr int RV = LY::RV, MTS = LY::MTS, KSTEPS = LY::KSTEPS, NT = FT::NT;
+    constexpr int SLOT = LY::HIDDEN + WP;
+    static_assert(LY::FIRST <= LY::HIDDEN && LY::OUTW + 4 <= SLOT, "slot size");
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthreads >> 6;
+    const int g = lane / TM;
+    const IndexEntry e = w.e;
+    const int L = e.n_layers;
+    const int K = (int)((a.lds_bytes >> 2) / (uint32_t)SLOT);        // layers per group; the host launches with room for one at least
+    const uint32_t *rec = (const uint32_t *)(a.blob + e.off);
+    const float pre = a.pre;
+    float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};
+    if (a.affine)
+        for (int q = 0; q < 6; ++q) af[q] = a.affine[(size_t)w.slot * 6 + q];
+
+    for (uint32_t t0 = w.tile0; t0 < w.tile1; t0 += (uint32_t)nwaves) {
+        const uint32_t tile = t0 + (uint32_t)wave;
+        const bool active = tile < w.tile1;                            // the same for a whole wavefront
+        float Bv[NT][KSTEPS];
+        for (int l0 = 0; l0 < L; l0 += K) {
+            const int l1 = l0 + K < L ? l0 + K : L;
+            __syncthreads();                                           // every wavefront is done with the previous group
+            for (int q = tid; q < (l1 - l0) * SLOT; q += nthreads) lds[q] = 0.0f;
+            __syncthreads();
+            ExpandShare sh = expand_share(rec, l0, l1, wave, nwaves);
+            for (int l = l0; l < l1; ++l) expand_slot<TM, WP>(lds + (l - l0) * SLOT, rec, L, l, pre, lane, sh);
+            __syncthreads();
+            if (!active) continue;
+            for (int l = l0; l < l1; ++l) {
+                const float *wb = lds + (l - l0) * SLOT, *bb = wb + LY::HIDDEN;
+                if (l == 0) {
+                    float bx[NT];
+                    FT::coords(a, af, tile, lane, bx);
+                    FT::first(Bv, wb + lane * MTS, bb + g * RV, bx);
+                } else if (l < L - 1) {
+                    FT::hidden(Bv, wb + lane * MTS, bb + g * RV);
+                } else {
+                    FT::output(a, Bv, wb + g * KSTEPS * 4, bb[0], bb[1], bb[2], tile, lane, w.plane0);
+                }
+            }
+        }
     }
 }
 
@@ -522,35 +650,48 @@ __global__ __launch_bounds__(NTHREADS) void decode_any_kernel(const DecodeArgs a
     }
 }
 
-// ---- debug export of the expand stage -----------------------------------------------------
+// The streamed form, one width class per launch, one wavefront per SIMD (the activations stay in registers
+// across the expansion of the next group of layers).
+constexpr int kStreamThreads = 256;
 template <int TM, int WP>
-__global__ __launch_bounds__(256) void dequant_debug_kernel(const uint8_t *blob, int64_t id, int layer,
-                                                            uint32_t stage_off, float *out, float *bias_out) {
+__global__ __launch_bounds__(kStreamThreads) void decode_stream_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    Work w;
+    if (!decode_prologue(a, w)) return;
+    decode_stream_body<TM, WP>(a, w, lds);
+}
+
+// ---- debug export of the expand stage -----------------------------------------------------
+// One layer, straight from the packed record in global memory into one slot (any depth fits), read back out of
+// the layout the decode kernels use.
+template <int TM, int WP>
+__global__ __launch_bounds__(256) void dequant_debug_kernel(const uint8_t *blob, int64_t id, int layer, float *out, float *bias_out) {
     typedef Layout<TM, WP> LY;
+    constexpr int SLOT = LY::HIDDEN + WP;
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthreads >> 6;
     const IndexEntry e = *(const IndexEntry *)(blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
     const int L = e.n_layers;
-    uint32_t *stage = (uint32_t *)(lds + stage_off);
-    {
-        const uint4 *src = (const uint4 *)(blob + e.off);
-        uint4 *dst = (uint4 *)stage;
-        for (uint32_t q = tid; q < (e.nbytes >> 4); q += nthreads) dst[q] = src[q];
-    }
-    expand_model<TM, WP>(lds, stage, L, 1.0f, tid, nthreads);
-    const LayerRec r = *(const LayerRec *)(stage + layer * (sizeof(LayerRec) / 4));
+    const uint32_t *rec = (const uint32_t *)(blob + e.off);
+    for (int q = tid; q < SLOT; q += nthreads) lds[q] = 0.0f;
+    __syncthreads();
+    ExpandShare sh = expand_share(rec, layer, layer + 1, wave, nwaves);
+    expand_slot<TM, WP>(lds, rec, L, layer, 1.0f, lane, sh);
+    __syncthreads();
+    const LayerRec r = *(const LayerRec *)(rec + layer * (sizeof(LayerRec) / 4));
     const int n_in = r.n_in, cnt = r.n_in * r.n_out;
     for (int k = tid; k < cnt; k += nthreads) {
         const int o = k / n_in, i = k - o * n_in;
         float v;
-        if (layer == L - 1) v = lds[LY::off_out(L) + LY::idx_out(o, i)];
-        else if (layer == 0) v = lds[LY::off_first() + LY::idx_first(o, i)];
-        else v = lds[LY::off_hidden(L, layer) + LY::idx_hidden(o, i)];
+        if (layer == L - 1) v = lds[LY::idx_out(o, i)];
+        else if (layer == 0) v = lds[LY::idx_first(o, i)];
+        else v = lds[LY::idx_hidden(o, i)];
         out[k] = v;
     }
     if (bias_out)
         for (int o = tid; o < r.n_out; o += nthreads)
-            bias_out[o] = (layer == L - 1) ? lds[LY::off_outb(L) + o] : lds[LY::off_bias(layer) + LY::idx_bias(o)];
+            bias_out[o] = (layer == L - 1) ? lds[LY::HIDDEN + o] : lds[LY::HIDDEN + LY::idx_bias(o)];
 }
 
 }  // namespace rinr

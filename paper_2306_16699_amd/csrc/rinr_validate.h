@@ -18,4 +18,8 @@ struct StoreSummary {
 
 int validate_blob(const void *host_blob, size_t bytes, StoreSummary *sum);
 
+// Worst-case output error of the reduced-precision decode modes over a validated blob (maximum over its models):
+// bounds[0] for one fp16 value per hidden activation, bounds[1] with fp16 hidden weights as well.
+void store_error_bounds(const void *host_blob, const StoreSummary &sum, double bounds[2]);
+
 }  // namespace rinr

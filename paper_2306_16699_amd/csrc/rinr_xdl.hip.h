@@ -112,18 +112,35 @@ __host__ __device__ inline uint32_t xdl_model_bytes(int cls, int n_layers, int n
            wp * wp * 2u * (uint32_t)(n_int + 2 * n_raw) + 2u * out;
 }
 
-template <int TM, int WP, bool W16>
-__device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec, int L, float pre, int tid, int nthreads,
-                                                 uint32_t total_bytes) {
+// Builds the operand blocks of layers [l0, l1) in LDS and their XLayer entries tab[l].  `rec` is the model record:
+// the staged copy in LDS, or the record itself in global memory.
+//   SLOTTED == false (resident model, l0 = 0, l1 = L): table, all bias tiles, then the blocks back to back.
+//   SLOTTED == true  (streamed model): table, then one fixed-size slot per layer of the group: bias tile, blocks.
+// zero_bytes from the start of LDS are cleared first (padding rows and columns, pruned weights).  Ends with a barrier.
+template <int TM, int WP> struct XSlot {
+    typedef XLayout<TM, WP> LY;
+    static constexpr int BLOCKS = 2 * LY::HID > LY::FIRST ? (2 * LY::HID > 2 * LY::OUT ? 2 * LY::HID : 2 * LY::OUT)
+                                                          : (LY::FIRST > 2 * LY::OUT ? LY::FIRST : 2 * LY::OUT);
+    static constexpr int BIAS = WP * 4 > LY::OUTB ? WP * 4 : LY::OUTB;
+    static constexpr int BYTES = BIAS + BLOCKS;
+};
+
+template <int TM, int WP, bool W16, bool SLOTTED>
+__device__ __forceinline__ void xdl_expand_layers(char *lds, const uint32_t *rec, int L, int l0, int l1, float pre, int tid,
+                                                  int nthreads, uint32_t zero_bytes) {
     typedef XLayout<TM, WP> LY;
     XLayer *tab = (XLayer *)lds;
-    for (uint32_t q = tid; q < (total_bytes >> 2); q += nthreads) ((uint32_t *)lds)[q] = 0u;
+    for (uint32_t q = tid; q < (zero_bytes >> 2); q += nthreads) ((uint32_t *)lds)[q] = 0u;
     __syncthreads();
     if (tid == 0) {
         uint32_t bias = LY::TABLE;
         uint32_t cur = LY::TABLE + (uint32_t)(L - 1) * WP * 4u + LY::OUTB;
-        for (int l = 0; l < L; ++l) {
+        for (int l = l0; l < l1; ++l) {
             const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
+            if (SLOTTED) {
+                bias = LY::TABLE + (uint32_t)(l - l0) * XSlot<TM, WP>::BYTES;
+                cur = bias + XSlot<TM, WP>::BIAS;
+            }
             XLayer e;
             e.off_bias = bias;
             bias += l < L - 1 ? WP * 4 : LY::OUTB;
@@ -140,8 +157,8 @@ __device__ __forceinline__ void xdl_expand_model(char *lds, const uint32_t *rec,
     }
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, nwaves = nthreads >> 6;
-    ExpandShare sh = expand_share(rec, L, wave, nwaves);
-    for (int l = 0; l < L; ++l) {
+    ExpandShare sh = expand_share(rec, l0, l1, wave, nwaves);
+    for (int l = l0; l < l1; ++l) {
         const LayerRec r = *(const LayerRec *)(rec + l * (sizeof(LayerRec) / 4));
         const XLayer e = tab[l];
         _Float16 *hi = (_Float16 *)(lds + e.off_hi), *lo = (_Float16 *)(lds + e.off_lo);
@@ -337,24 +354,138 @@ __device__ __forceinline__ void xdl_layer(XHalf<TM, WP> &X, XHalf<TM, WP> &Y, co
     xdl_epilogue<TM, WP, A16>(X, scale, neg1);
 }
 
+// The slot's augmentation map (every lane holds it alike), in scalar registers.
+struct XUniform {
+    float af0, af1, af2, af3, af4, af5;
+};
+__device__ __forceinline__ XUniform xdl_uniform(const DecodeArgs &a, uint32_t slot) {
+    XUniform u;
+    u.af0 = 1.0f; u.af1 = 0.0f; u.af2 = 0.0f; u.af3 = 0.0f; u.af4 = 1.0f; u.af5 = 0.0f;   // augmentation: this slot's map of the sampling grid
+    if (a.affine) {
+        const float *m = a.affine + (size_t)slot * 6;
+        u.af0 = uniform_f(m[0]); u.af1 = uniform_f(m[1]); u.af2 = uniform_f(m[2]);
+        u.af3 = uniform_f(m[3]); u.af4 = uniform_f(m[4]); u.af5 = uniform_f(m[5]);
+    }
+    return u;
+}
+
+// ---- first layer: every lane forms the coordinates of its own pixel (tile * 64 + lane) as hi/lo halfs in
+//      k slots (xh, yh, xl, yl, xh, yh, 0, 0); the MFMA of pixel tile q uses the weight variant whose
+//      non-zero k slots are lane group q's, so one operand register set serves all pixel tiles.
+//      Per-lane values that only the first and the last layer use are derived again for every tile
+//      (the empty asm keeps them from being hoisted): held across the hidden layers they would
+//      push the kernel over its register budget.
+template <int TM, int WP>
+__device__ __forceinline__ void xdl_first(XHalf<TM, WP> &X, XHalf<TM, WP> &Y, const DecodeArgs &a, const XUniform &u, const char *lds,
+                                          const XLayer e0, uint32_t tile, int lane) {
+    typedef XLayout<TM, WP> LY;
+    typedef XTile<TM> T;
+    typedef typename T::acc_t acc_t;
+    constexpr int MT = LY::MT, G = LY::G, NTH = XHalf<TM, WP>::NTH;
+    const int g = lane / TM;
+    float lo_v = a.lo, af2 = u.af2, af5 = u.af5;        // second uniform operand of an fma: copied to a vector register at the use
+    asm volatile("" : "+s"(lo_v), "+s"(af2), "+s"(af5));
+    const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
+    const acc_t *bt = (const acc_t *)(lds + e0.off_bias) + g;
+    uint32_t p = (tile << 6) + (uint32_t)lane;
+    p = min(p, a.HW - 1);
+    const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
+    const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, lo_v);
+    const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, lo_v);
+    const float x = fmaf(u.af0, x0, fmaf(u.af1, y0, af2)), y = fmaf(u.af3, x0, fmaf(u.af4, y0, af5));
+    const _Float16 xh = (_Float16)x, yh = (_Float16)y;
+    const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
+    const _Float16 z = (_Float16)0.0f;
+    const h8v b0 = {xh, yh, xl, yl, xh, yh, z, z};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const acc_t c = bt[mt * G];
+#pragma unroll
+        for (int nt = 0; nt < NTH; ++nt) {
+            X.D[nt][mt] = T::mfma(a0[(nt * MT + mt) * 64], b0, c);
+            Y.D[nt][mt] = T::mfma(a0[((NTH + nt) * MT + mt) * 64], b0, c);
+        }
+    }
+}
+
+// ---- output layer width -> 3: one TM-row tile with channel c in row 4c.  At TM = 16 that is
+//      register 0 of lane group c; at TM = 32 registers 0 (R) and 4 (B) of group 0, register 0 (G) of group 1.
+//      Then clamp, optional normalisation and the NCHW store.
+template <int TM, int WP, bool A16>
+__device__ __forceinline__ void xdl_output(const XHalf<TM, WP> &X, const XHalf<TM, WP> &Y, const DecodeArgs &a, float ns0, float ns1,
+                                           float ns2, float nb0, float nb1, float nb2, const char *lds, const XLayer eo,
+                                           uint32_t tile, int lane, size_t plane0) {
+    typedef XLayout<TM, WP> LY;
+    typedef XTile<TM> T;
+    typedef typename T::acc_t acc_t;
+    constexpr int KJ = LY::KJ, K16 = LY::K16, NTH = XHalf<TM, WP>::NTH;
+    const int go = lane / TM, no = lane % TM;
+    const h8v *ah = (const h8v *)(lds + eo.off_hi) + lane;
+    const h8v *al = (const h8v *)(lds + eo.off_lo) + lane;
+    const h4v *ah4 = (const h4v *)(lds + eo.off_hi + KJ * 1024) + lane;
+    const h4v *al4 = (const h4v *)(lds + eo.off_lo + KJ * 1024) + lane;
+    const acc_t c = ((const acc_t *)(lds + eo.off_bias))[go];
+    acc_t O[2 * NTH];
+#pragma unroll
+    for (int nt = 0; nt < 2 * NTH; ++nt) O[nt] = c;
+#pragma unroll
+    for (int j = 0; j < KJ; ++j) {
+        const h8v av = ah[j * 64], aw = al[j * 64];
+#pragma unroll
+        for (int nt = 0; nt < 2 * NTH; ++nt) {
+            const h8v bh = nt < NTH ? X.Hh[nt % NTH][j] : Y.Hh[nt % NTH][j];
+            O[nt] = T::mfma(av, bh, O[nt]);
+            if (!A16) O[nt] = T::mfma(av, nt < NTH ? X.Hl[nt % NTH][j] : Y.Hl[nt % NTH][j], O[nt]);
+            O[nt] = T::mfma(aw, bh, O[nt]);
+        }
+    }
+    if (K16) {
+        const h4v av = ah4[0], aw = al4[0];
+#pragma unroll
+        for (int nt = 0; nt < 2 * NTH; ++nt) {
+            const h4v bh = nt < NTH ? X.Hh4[nt % NTH] : Y.Hh4[nt % NTH];
+            O[nt] = T::mfma_half(av, bh, O[nt]);
+            if (!A16) O[nt] = T::mfma_half(av, nt < NTH ? X.Hl4[nt % NTH] : Y.Hl4[nt % NTH], O[nt]);
+            O[nt] = T::mfma_half(aw, bh, O[nt]);
+        }
+    }
+#pragma unroll
+    for (int nt = 0; nt < 2 * NTH; ++nt) {
+        const uint32_t p = (tile << 6) + nt * TM + no;
+        constexpr int NS = TM == 16 ? 1 : 2;     // values a lane may store per pixel tile
+#pragma unroll
+        for (int k = 0; k < NS; ++k) {
+            const int ch = TM == 16 ? go : (go == 0 ? 2 * k : 1);
+            const bool live = TM == 16 ? go < 3 : (go == 0 || k == 0);
+            float r = O[nt][TM == 16 ? 0 : 4 * k];
+            if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
+            if (a.normalize) r = fmaf(r, ch == 0 ? ns0 : (ch == 1 ? ns1 : ns2), ch == 0 ? nb0 : (ch == 1 ? nb1 : nb2));
+            if (live && p < a.HW) {
+                const uint32_t at = (uint32_t)ch * a.HW + p;  // within the slot's three planes: 3 HW < 2^32 is checked by the host
+                if (a.out_f32) (a.out_f32 + plane0)[at] = r;
+                if (a.out_u8) (a.out_u8 + plane0)[at] = (uint8_t)rintf(255.0f * r);
+            }
+        }
+    }
+}
+
+// Resident form: the model is expanded once per workgroup; a wavefront takes one 64-pixel tile at a time through all
+// layers.
 template <int TM, int WP, int MODE_>
 __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, float *lds_f) {
     constexpr bool W16 = (MODE_ & kWeight16) != 0;
     constexpr int MODE = W16 ? (int)kHiddenAllRaw : (MODE_ & 3);      // all-fp16: one form for every hidden layer, no scale
     constexpr bool A16 = (MODE_ & kAct16) != 0 || W16;
-    typedef XLayout<TM, WP> LY;
-    typedef XTile<TM> T;
-    typedef typename T::acc_t acc_t;
     typedef XHalf<TM, WP> Half;
-    constexpr int KJ = LY::KJ, K16 = LY::K16, MT = LY::MT, G = LY::G, NTH = Half::NTH;
     char *lds = (char *)lds_f;
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const uint32_t slot = w.slot, tile0 = w.tile0, tile1 = w.tile1;
+    const uint32_t tile0 = w.tile0, tile1 = w.tile1;
     const size_t plane0 = w.plane0;
     const IndexEntry e = w.e;
     const int L = e.n_layers;
 
-    uint32_t *stage = (uint32_t *)(lds_f + a.stage_off[WP / 16]);
+    // the packed record is staged at the end of the workgroup's LDS, the operand blocks are built at the start
+    uint32_t *stage = (uint32_t *)(lds + (a.lds_bytes - e.nbytes));
     {
         const uint4 *src = (const uint4 *)(a.blob + e.off);
         uint4 *dst = (uint4 *)stage;
@@ -363,7 +494,7 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     // Tiles are handed out through a counter in LDS (it reuses the first word of the staging area,
     // which is dead once the model is expanded): the SIMD arbiter favours its older wavefront, so
     // with a fixed split the favoured waves would finish early and leave the others running alone.
-    xdl_expand_model<TM, WP, W16>(lds, stage, L, a.pre, tid, nthreads, a.stage_off[WP / 16] << 2);
+    xdl_expand_layers<TM, WP, W16, false>(lds, stage, L, 0, L, a.pre, tid, nthreads, a.lds_bytes - e.nbytes);
     uint32_t *next_tile = stage;
     if (tid == 0) *next_tile = tile0 + (nthreads >> 6);
     __syncthreads();
@@ -372,50 +503,17 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
     const XLayer *tab = (const XLayer *)lds;
     const float neg1 = a.neg1;
     const XLayer e0 = uniform_layer(tab[0]), eo = uniform_layer(tab[L - 1]);
+    const XUniform u = xdl_uniform(a, w.slot);
     // per-channel normalisation constants as values (not as an address chosen per lane)
     const float ns0 = uniform_f(a.ns[0]), ns1 = uniform_f(a.ns[1]), ns2 = uniform_f(a.ns[2]);
     const float nb0 = uniform_f(a.nb[0]), nb1 = uniform_f(a.nb[1]), nb2 = uniform_f(a.nb[2]);
-    float af[6] = {1.0f, 0.0f, 0.0f, 0.0f, 1.0f, 0.0f};      // augmentation: this slot's map of the sampling grid
-    if (a.affine)
-        for (int q = 0; q < 6; ++q) af[q] = uniform_f(a.affine[(size_t)slot * 6 + q]);
 
     for (uint32_t tile = tile0 + wave; tile < tile1;) {
         Half X, Y;
-        // Per-lane values that only the first and the last layer use are derived again for every tile
-        // (the empty asm keeps them from being hoisted): held across the hidden layers they would
-        // push the kernel over its register budget.
         uint32_t ones = ~0u;
         asm volatile("" : "+s"(ones));
         int lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
-        const int g = lane / TM;
-        float lo_v = a.lo, af2 = af[2], af5 = af[5];        // second uniform operand of an fma: copied to a vector register at the use
-        asm volatile("" : "+s"(lo_v), "+s"(af2), "+s"(af5));
-        // ---- first layer: every lane forms the coordinates of its own pixel (tile * 64 + lane) as hi/lo halfs in
-        //      k slots (xh, yh, xl, yl, xh, yh, 0, 0); the MFMA of pixel tile q uses the weight variant whose
-        //      non-zero k slots are lane group q's, so one operand register set serves all pixel tiles
-        {
-            const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
-            const acc_t *bt = (const acc_t *)(lds + e0.off_bias) + g;
-            uint32_t p = (tile << 6) + (uint32_t)lane;
-            p = min(p, a.HW - 1);
-            const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
-            const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, lo_v);
-            const float y0 = fmaf(a.span, (float)(2 * row + 1) * a.inv2H, lo_v);
-            const float x = fmaf(af[0], x0, fmaf(af[1], y0, af2)), y = fmaf(af[3], x0, fmaf(af[4], y0, af5));
-            const _Float16 xh = (_Float16)x, yh = (_Float16)y;
-            const _Float16 xl = (_Float16)(x - (float)xh), yl = (_Float16)(y - (float)yh);
-            const _Float16 z = (_Float16)0.0f;
-            const h8v b0 = {xh, yh, xl, yl, xh, yh, z, z};
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const acc_t c = bt[mt * G];
-#pragma unroll
-                for (int nt = 0; nt < NTH; ++nt) {
-                    X.D[nt][mt] = T::mfma(a0[(nt * MT + mt) * 64], b0, c);
-                    Y.D[nt][mt] = T::mfma(a0[((NTH + nt) * MT + mt) * 64], b0, c);
-                }
-            }
-        }
+        xdl_first<TM, WP>(X, Y, a, u, lds, e0, tile, lane);
         xdl_epilogue<TM, WP, A16>(X, 1.0f, neg1);
         // ---- hidden layers, software-pipelined over the two halves:
         //      matrix work of X(l) with the sine/split of Y(l-1), then matrix work of Y(l) with the sine/split of X(l)
@@ -446,61 +544,64 @@ __device__ __forceinline__ void xdl_body(const DecodeArgs &a, const Work &w, flo
         xdl_epilogue<TM, WP, A16>(Y, scale_prev, neg1);
         asm volatile("" : "+s"(ones));           // pixel indices and addresses: derived again rather than kept
         lane = (int)__builtin_amdgcn_mbcnt_hi(ones, __builtin_amdgcn_mbcnt_lo(ones, 0u));
-        const int go = lane / TM, no = lane % TM;
-        // ---- output layer width -> 3: one TM-row tile with channel c in row 4c.  At TM = 16 that is
-        //      register 0 of lane group c; at TM = 32 registers 0 (R) and 4 (B) of group 0, register 0 (G) of group 1.
-        {
-            const h8v *ah = (const h8v *)(lds + eo.off_hi) + lane;
-            const h8v *al = (const h8v *)(lds + eo.off_lo) + lane;
-            const h4v *ah4 = (const h4v *)(lds + eo.off_hi + KJ * 1024) + lane;
-            const h4v *al4 = (const h4v *)(lds + eo.off_lo + KJ * 1024) + lane;
-            const acc_t c = ((const acc_t *)(lds + eo.off_bias))[go];
-            acc_t O[2 * NTH];
-#pragma unroll
-            for (int nt = 0; nt < 2 * NTH; ++nt) O[nt] = c;
-#pragma unroll
-            for (int j = 0; j < KJ; ++j) {
-                const h8v av = ah[j * 64], aw = al[j * 64];
-#pragma unroll
-                for (int nt = 0; nt < 2 * NTH; ++nt) {
-                    const h8v bh = nt < NTH ? X.Hh[nt % NTH][j] : Y.Hh[nt % NTH][j];
-                    O[nt] = T::mfma(av, bh, O[nt]);
-                    if (!A16) O[nt] = T::mfma(av, nt < NTH ? X.Hl[nt % NTH][j] : Y.Hl[nt % NTH][j], O[nt]);
-                    O[nt] = T::mfma(aw, bh, O[nt]);
-                }
-            }
-            if (K16) {
-                const h4v av = ah4[0], aw = al4[0];
-#pragma unroll
-                for (int nt = 0; nt < 2 * NTH; ++nt) {
-                    const h4v bh = nt < NTH ? X.Hh4[nt % NTH] : Y.Hh4[nt % NTH];
-                    O[nt] = T::mfma_half(av, bh, O[nt]);
-                    if (!A16) O[nt] = T::mfma_half(av, nt < NTH ? X.Hl4[nt % NTH] : Y.Hl4[nt % NTH], O[nt]);
-                    O[nt] = T::mfma_half(aw, bh, O[nt]);
-                }
-            }
-#pragma unroll
-            for (int nt = 0; nt < 2 * NTH; ++nt) {
-                const uint32_t p = (tile << 6) + nt * TM + no;
-                constexpr int NS = TM == 16 ? 1 : 2;     // values a lane may store per pixel tile
-#pragma unroll
-                for (int k = 0; k < NS; ++k) {
-                    const int ch = TM == 16 ? go : (go == 0 ? 2 * k : 1);
-                    const bool live = TM == 16 ? go < 3 : (go == 0 || k == 0);
-                    float r = O[nt][TM == 16 ? 0 : 4 * k];
-                    if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
-                    if (a.normalize) r = fmaf(r, ch == 0 ? ns0 : (ch == 1 ? ns1 : ns2), ch == 0 ? nb0 : (ch == 1 ? nb1 : nb2));
-                    if (live && p < a.HW) {
-                        const uint32_t at = (uint32_t)ch * a.HW + p;  // within the slot's three planes: 3 HW < 2^32 is checked by the host
-                        if (a.out_f32) (a.out_f32 + plane0)[at] = r;
-                        if (a.out_u8) (a.out_u8 + plane0)[at] = (uint8_t)rintf(255.0f * r);
-                    }
-                }
-            }
-        }
+        xdl_output<TM, WP, A16>(X, Y, a, ns0, ns1, ns2, nb0, nb1, nb2, lds, eo, tile, lane, plane0);
         uint32_t nt_ = 0;
         if (lane == 0) nt_ = atomicAdd(next_tile, 1u);
         tile = __builtin_amdgcn_readfirstlane(nt_);
+    }
+}
+
+// Streamed form, for a model whose operand blocks do not fit LDS: the layers go through LDS in groups of as many
+// slots as fit.  Every wavefront keeps one tile in registers (both halves, mid-pipeline: X holds activations, Y
+// accumulators awaiting their sine); for each group the workgroup builds the group's blocks straight from the
+// packed record in global memory, then every wavefront takes its tile through the group's layers.
+template <int TM, int WP, int MODE_>
+__device__ __forceinline__ void xdl_stream_body(const DecodeArgs &a, const Work &w, float *lds_f) {
+    constexpr bool W16 = (MODE_ & kWeight16) != 0;
+    constexpr bool A16 = (MODE_ & kAct16) != 0 || W16;
+    typedef XLayout<TM, WP> LY;
+    typedef XHalf<TM, WP> Half;
+    char *lds = (char *)lds_f;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthreads >> 6;
+    const IndexEntry e = w.e;
+    const int L = e.n_layers;
+    const int K = (int)((a.lds_bytes - LY::TABLE) / (uint32_t)XSlot<TM, WP>::BYTES);   // layers per group (>= 1 by the host's launch size)
+    const uint32_t *rec = (const uint32_t *)(a.blob + e.off);
+    const XLayer *tab = (const XLayer *)lds;
+    const float neg1 = a.neg1;
+    const XUniform u = xdl_uniform(a, w.slot);
+    // per-channel normalisation constants as values (not as an address chosen per lane)
+    const float ns0 = uniform_f(a.ns[0]), ns1 = uniform_f(a.ns[1]), ns2 = uniform_f(a.ns[2]);
+    const float nb0 = uniform_f(a.nb[0]), nb1 = uniform_f(a.nb[1]), nb2 = uniform_f(a.nb[2]);
+
+    for (uint32_t t0 = w.tile0; t0 < w.tile1; t0 += (uint32_t)nwaves) {
+        const uint32_t tile = t0 + (uint32_t)wave;
+        const bool active = tile < w.tile1;                            // the same for a whole wavefront
+        Half X, Y;
+        float scale_prev = 1.0f;
+        for (int l0 = 0; l0 < L; l0 += K) {
+            const int l1 = l0 + K < L ? l0 + K : L;
+            __syncthreads();                                           // every wavefront is done with the previous group
+            xdl_expand_layers<TM, WP, W16, true>(lds, rec, L, l0, l1, a.pre, tid, nthreads,
+                                                 LY::TABLE + (uint32_t)(l1 - l0) * XSlot<TM, WP>::BYTES);
+            if (!active) continue;
+            for (int l = l0; l < l1; ++l) {
+                const XLayer el = uniform_layer(tab[l]);
+                if (l == 0) {
+                    xdl_first<TM, WP>(X, Y, a, u, lds, el, tile, lane);
+                    xdl_epilogue<TM, WP, A16>(X, 1.0f, neg1);
+                } else if (l < L - 1) {
+                    if (W16) xdl_layer<TM, WP, false, A16>(X, Y, lds, el, lane, lane / TM, 1.0f, 1.0f, neg1);
+                    else if (el.off_lo == 0) xdl_layer<TM, WP, false, A16>(X, Y, lds, el, lane, lane / TM, scale_prev, el.scale, neg1);
+                    else xdl_layer<TM, WP, true, A16>(X, Y, lds, el, lane, lane / TM, scale_prev, el.scale, neg1);
+                    scale_prev = W16 ? 1.0f : el.scale;
+                } else {
+                    xdl_epilogue<TM, WP, A16>(Y, scale_prev, neg1);
+                    xdl_output<TM, WP, A16>(X, Y, a, ns0, ns1, ns2, nb0, nb1, nb2, lds, el, tile, lane, w.plane0);
+                }
+            }
+        }
     }
 }
 
@@ -526,6 +627,60 @@ __global__ __launch_bounds__(NTHREADS) void decode_xdl_any_kernel(const DecodeAr
         default: xdl_body<32, 64, MODE>(a, w, lds_f); break;    // 32-row tiles: measured faster here, slower in the one-class kernel;
                                                                 // the layout is smaller than the 16-row one the host sizes LDS for
     }
+}
+
+// The streamed form: one width class per launch, one wavefront per SIMD.  MODE: 0 (hi+lo activations, any kind of
+// hidden layer), kAct16, or kAct16 | kWeight16.
+template <int CLS, int MODE>
+__global__ __launch_bounds__(kStreamThreads) void decode_xdl_stream_kernel(const DecodeArgs a) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    Work w;
+    if (!decode_prologue(a, w)) return;
+    xdl_stream_body<xdl_tile_rows(CLS), 16 * CLS, MODE>(a, w, lds_f);
+}
+
+// ---- debug export of the split-precision operand blocks (see rinr_debug_dequant_split) ----------------------------
+template <int TM, int WP, bool W16>
+__global__ __launch_bounds__(256) void xdl_debug_kernel(const uint8_t *blob, int64_t id, int layer, uint32_t lds_bytes,
+                                                        float *hi_out, float *lo_out, float *bias_out, float *scale_out) {
+    typedef XLayout<TM, WP> LY;
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];
+    char *lds = (char *)lds_f;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const IndexEntry e = *(const IndexEntry *)(blob + sizeof(StoreHeader) + (size_t)id * sizeof(IndexEntry));
+    const int L = e.n_layers;
+    const uint32_t *rec = (const uint32_t *)(blob + e.off);
+    // one layer at a time in the slotted layout, straight from global memory: any depth fits
+    xdl_expand_layers<TM, WP, W16, true>(lds, rec, L, layer, layer + 1, 1.0f, tid, nthreads, lds_bytes);
+    const XLayer el = ((const XLayer *)lds)[layer];
+    const LayerRec r = *(const LayerRec *)(rec + layer * (sizeof(LayerRec) / 4));
+    const _Float16 *hi = (const _Float16 *)(lds + el.off_hi), *lo = (const _Float16 *)(lds + el.off_lo);
+    const float *bt = (const float *)(lds + el.off_bias);
+    const int n_in = r.n_in, cnt = r.n_in * r.n_out;
+    const float nan = __uint_as_float(0x7FC00000u);
+    for (int k = tid; k < cnt; k += nthreads) {
+        const int o = k / n_in, i = k - o * n_in;
+        float h, l;
+        if (layer == L - 1) {
+            h = (float)hi[LY::idx_out(o, i)];
+            l = (float)lo[LY::idx_out(o, i)];
+        } else if (layer == 0) {
+            h = (float)hi[LY::idx_first(0, o, i)];
+            l = (float)hi[LY::idx_first(0, o, 4 + i)];
+            for (int q = 0; q < LY::G; ++q) {          // every copy must agree
+                if ((float)hi[LY::idx_first(q, o, i)] != h || (float)hi[LY::idx_first(q, o, 2 + i)] != h) h = nan;
+                if ((float)hi[LY::idx_first(q, o, 4 + i)] != l) l = nan;
+            }
+        } else {
+            h = (float)hi[LY::idx_hidden(o, i)];
+            l = el.off_lo ? (float)lo[LY::idx_hidden(o, i)] : 0.0f;
+        }
+        hi_out[k] = h;
+        lo_out[k] = l;
+    }
+    if (bias_out)
+        for (int o = tid; o < r.n_out; o += nthreads) bias_out[o] = bt[LY::idx_bias(layer == L - 1 ? 4 * o : o)];
+    if (scale_out && tid == 0) *scale_out = el.scale;
 }
 
 }  // namespace rinr

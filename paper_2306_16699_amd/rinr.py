@@ -13,7 +13,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-SO_PATH = os.environ.get("RINR_LIB") or os.path.join(_HERE, "librinr.so")   # RINR_LIB: load another build of the library
+SO_PATH = os.path.join(_HERE, "librinr.so")
 
 OK = 0
 OUT_F32, OUT_U8, OUT_F32_AND_U8 = 1, 2, 3
@@ -22,11 +22,13 @@ FLAG_FP32_MFMA = 2
 FLAG_NORMALIZE = 4
 FLAG_FP16_ACT = 8
 FLAG_FP16_ALL = 16
+FLAG_FP16_UNCHECKED = 32
+FAMILIES = ("split precision (fp16 hi+lo pairs)", "fp32 MFMA", "fp16 activations", "fp16 weights and activations")
 E_NULL, E_ARG, E_MODEL, E_SIZE, E_FORMAT, E_UNSUPPORTED, E_ALIGN, E_HIP = -1, -2, -3, -4, -5, -6, -7, -8
 
-EXPORTS = ["rinr_pack_size", "rinr_pack", "rinr_unpack_layer", "rinr_store_open", "rinr_store_close",
-           "rinr_store_info", "rinr_decode_batch", "rinr_decode_batch_ex", "rinr_store_status",
-           "rinr_debug_dequant", "rinr_last_launch_info", "rinr_tune", "rinr_strerror",
+EXPORTS = ["rinr_pack_size", "rinr_pack", "rinr_unpack_layer", "rinr_store_open", "rinr_store_open_ex", "rinr_store_close",
+           "rinr_store_info", "rinr_store_error_bounds", "rinr_decode_batch", "rinr_decode_batch_ex", "rinr_store_status",
+           "rinr_debug_dequant", "rinr_debug_dequant_split", "rinr_last_launch_info", "rinr_strerror",
            "rinr_last_hip_error", "rinr_version", "rinr_decode_workspace_bytes"]
 
 
@@ -43,10 +45,15 @@ class StoreOpts(C.Structure):
     _fields_ = [("w0", C.c_float), ("coord_lo", C.c_float), ("coord_hi", C.c_float)]
 
 
+class OpenOpts(C.Structure):
+    _fields_ = [("fp32_tile_rows", C.c_int32), ("lds_budget", C.c_int32)]
+
+
 class DecodeOpts(C.Structure):
     _fields_ = [("out_dtype", C.c_int32), ("flags", C.c_int32), ("out_u8", C.c_void_p), ("affine", C.c_void_p),
                 ("norm_scale", C.c_float * 3), ("norm_shift", C.c_float * 3), ("workspace", C.c_void_p),
-                ("workspace_bytes", C.c_size_t)]
+                ("workspace_bytes", C.c_size_t), ("launch_threads", C.c_int32), ("launch_blocks_per_cu", C.c_int32),
+                ("one_grid_min_tiles", C.c_int32)]
 
 
 class RinrError(RuntimeError):
@@ -70,14 +77,16 @@ def lib():
         L.rinr_pack.argtypes = [C.POINTER(ModelDesc), i64, C.POINTER(StoreOpts), vp, C.c_size_t]
         L.rinr_unpack_layer.argtypes = [vp, C.c_size_t, i64, i32, vp, vp, vp, vp, C.POINTER(i32 * 5), C.POINTER(C.c_float)]
         L.rinr_store_open.argtypes = [vp, vp, C.c_size_t, C.POINTER(vp)]
+        L.rinr_store_open_ex.argtypes = [vp, vp, C.c_size_t, C.POINTER(OpenOpts), C.POINTER(vp)]
+        L.rinr_store_error_bounds.argtypes = [vp, C.POINTER(C.c_float * 2)]
         L.rinr_store_close.argtypes = [vp]
         L.rinr_store_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
         L.rinr_decode_batch.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.rinr_decode_batch_ex.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(DecodeOpts), vp]
         L.rinr_store_status.argtypes = [vp, C.POINTER(i64), vp]
         L.rinr_debug_dequant.argtypes = [vp, i64, i32, vp, vp, vp]
-        L.rinr_last_launch_info.argtypes = [vp, C.POINTER(i32 * 4)]
-        L.rinr_tune.argtypes = [C.c_int, C.c_int]
+        L.rinr_debug_dequant_split.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.rinr_last_launch_info.argtypes = [vp, C.POINTER(i32 * 6)]
         L.rinr_strerror.argtypes = [C.c_int]
         L.rinr_strerror.restype = C.c_char_p
         L.rinr_version.restype = C.c_char_p
@@ -175,10 +184,6 @@ def unpack_layer(blob: np.ndarray, model: int, layer: int):
                 codes=codes.reshape(n_out, n_in), f32=f32.reshape(n_out, n_in), keep=keep.reshape(n_out, n_in), bias=bias)
 
 
-def tune(knob: int, value: int):
-    _check(lib().rinr_tune(knob, value), "rinr_tune")
-
-
 def _stream_ptr(stream) -> Optional[int]:
     if stream is None:
         import torch
@@ -191,7 +196,8 @@ def _stream_ptr(stream) -> Optional[int]:
 class Store:
     """A device-resident dataset in weight format.  Holds the device blob (a torch uint8 tensor)."""
 
-    def __init__(self, blob: np.ndarray, device="cuda:0", validate_on_device: bool = False):
+    def __init__(self, blob: np.ndarray, device="cuda:0", validate_on_device: bool = False, fp32_tile_rows: int = 0,
+                 lds_budget: int = 0):
         import torch
         self._torch = torch
         self.device = torch.device(device)
@@ -199,8 +205,12 @@ class Store:
         with torch.cuda.device(self.device):
             self.dev_blob = torch.from_numpy(blob).to(self.device)
             h = C.c_void_p(0)
-            _check(lib().rinr_store_open(self.dev_blob.data_ptr(), None if validate_on_device else blob.ctypes.data,
-                                         blob.size, C.byref(h)), "rinr_store_open")
+            host = None if validate_on_device else blob.ctypes.data
+            if fp32_tile_rows or lds_budget:
+                oo = OpenOpts(fp32_tile_rows, lds_budget)
+                _check(lib().rinr_store_open_ex(self.dev_blob.data_ptr(), host, blob.size, C.byref(oo), C.byref(h)), "rinr_store_open_ex")
+            else:
+                _check(lib().rinr_store_open(self.dev_blob.data_ptr(), host, blob.size, C.byref(h)), "rinr_store_open")
         self._h = h
 
     def close(self):
@@ -219,6 +229,12 @@ class Store:
         _check(lib().rinr_store_info(self._h, C.byref(n), C.byref(w), C.byref(l)), "rinr_store_info")
         return n.value, w.value, l.value
 
+    def error_bounds(self):
+        """rinr_store_error_bounds: a-priori error bounds of FLAG_FP16_ACT and FLAG_FP16_ALL on this store."""
+        b = (C.c_float * 2)()
+        _check(lib().rinr_store_error_bounds(self._h, C.byref(b)), "rinr_store_error_bounds")
+        return float(b[0]), float(b[1])
+
     def decode_batch(self, image_ids, H: int, W: int, out=None, stream=None):
         """rinr_decode_batch: fp32 NCHW, clamped to [0, 1].  image_ids: int64 CUDA tensor."""
         torch = self._torch
@@ -230,13 +246,15 @@ class Store:
         return out
 
     def decode_batch_ex(self, image_ids, H: int, W: int, out_dtype: int = OUT_F32, flags: int = 0,
-                        out=None, out_u8=None, stream=None, affine=None, norm=None, workspace=None):
+                        out=None, out_u8=None, stream=None, affine=None, norm=None, workspace=None,
+                        threads: int = 0, blocks_per_cu: int = 0, one_grid_min_tiles: int = 0):
         """rinr_decode_batch_ex.  Returns out (and out_u8 for OUT_F32_AND_U8).
 
         workspace: uint8 CUDA tensor of >= workspace_bytes(n) bytes (heaviest-first order for ragged stores) or None;
 
         affine: float32 CUDA tensor [n, 6] (per-slot map of the sampling grid) or None;
-        norm: (scale[3], shift[3]) host numbers, sets FLAG_NORMALIZE."""
+        norm: (scale[3], shift[3]) host numbers, sets FLAG_NORMALIZE;
+        threads, blocks_per_cu, one_grid_min_tiles: launch shape (0 = the library's choice)."""
         torch = self._torch
         n = int(image_ids.numel())
         if out is None:
@@ -245,6 +263,7 @@ class Store:
         if out_dtype == OUT_F32_AND_U8 and out_u8 is None:
             out_u8 = torch.empty((n, 3, H, W), dtype=torch.uint8, device=self.device)
         o = DecodeOpts(out_dtype, flags, out_u8.data_ptr() if (out_u8 is not None and n) else None)
+        o.launch_threads, o.launch_blocks_per_cu, o.one_grid_min_tiles = threads, blocks_per_cu, one_grid_min_tiles
         if affine is not None:
             assert affine.dtype == torch.float32 and affine.is_contiguous() and tuple(affine.shape) == (n, 6)
             o.affine = affine.data_ptr() if n else None
@@ -273,7 +292,19 @@ class Store:
                "rinr_debug_dequant")
         return w, b
 
+    def debug_dequant_split(self, model: int, layer: int, n_in: int, n_out: int, fp16_weights: bool = False, stream=None):
+        """rinr_debug_dequant_split: (hi, lo, bias, scale) of the split-precision kernels' operand blocks."""
+        torch = self._torch
+        hi = torch.empty((n_out, n_in), dtype=torch.float32, device=self.device)
+        lo = torch.empty((n_out, n_in), dtype=torch.float32, device=self.device)
+        b = torch.empty((n_out,), dtype=torch.float32, device=self.device)
+        sc = torch.empty((1,), dtype=torch.float32, device=self.device)
+        _check(lib().rinr_debug_dequant_split(self._h, model, layer, 1 if fp16_weights else 0, hi.data_ptr(), lo.data_ptr(),
+                                              b.data_ptr(), sc.data_ptr(), _stream_ptr(stream)), "rinr_debug_dequant_split")
+        return hi, lo, b, sc
+
     def last_launch_info(self):
-        info = (C.c_int32 * 4)()
+        info = (C.c_int32 * 6)()
         _check(lib().rinr_last_launch_info(self._h, C.byref(info)), "rinr_last_launch_info")
-        return dict(launches=info[0], workgroups=info[1], threads=info[2], lds_bytes=info[3])
+        return dict(launches=info[0], workgroups=info[1], threads=info[2], lds_bytes=info[3], kernels=FAMILIES[info[4]],
+                    streamed=bool(info[5]))

@@ -10,14 +10,7 @@ from paper_2306_16699_amd import rinr, synth
 from paper_2306_16699_amd.synth import Layer, Model
 
 pytestmark = pytest.mark.gpu
-TOL = 1e-3
-
-
-def tol_of(mode):
-    """The opt-in single-fp16-activation mode rounds every hidden activation to 11 significant bits
-    (error up to 2^-12 each); the 40x output layer used here multiplies that (about 2e-3 observed).
-    Bar for that mode on these models: one step of the 8-bit output."""
-    return 1.0 / 255.0 if mode & (rinr.FLAG_FP16_ACT | rinr.FLAG_FP16_ALL) else TOL
+TOL = 1e-3          # every mode, every model: a reduced-precision mode runs only where its error bound allows it
 
 
 def image_like(models, gain=40.0):
@@ -56,13 +49,13 @@ def test_augmented_decode_matches_oracle(k, n, H, W):
     gain_n = float(np.abs(norm[0]).max())          # the normalisation scales the error with the value
     for mode in (0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL):
         got = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode, affine=aff_d, norm=norm).cpu().numpy()
-        assert np.abs(got - ref).max() <= tol_of(mode) * gain_n, (mode, np.abs(got - ref).max())
+        assert np.abs(got - ref).max() <= TOL * gain_n, (mode, np.abs(got - ref).max())
         geo = st.decode_batch_ex(ids, H, W, rinr.OUT_F32, mode | rinr.FLAG_NO_CLAMP, affine=aff_d).cpu().numpy()
-        assert np.abs(geo - ref_geo).max() <= tol_of(mode), (mode, np.abs(geo - ref_geo).max())
+        assert np.abs(geo - ref_geo).max() <= TOL, (mode, np.abs(geo - ref_geo).max())
         # uint8 output with a geometric map only (normalisation is fp32-only)
         f32, u8 = st.decode_batch_ex(ids, H, W, rinr.OUT_F32_AND_U8, mode, affine=aff_d)
         assert np.array_equal(u8.cpu().numpy(), np.rint(255.0 * f32.cpu().numpy()).astype(np.uint8))
-        assert np.abs(f32.cpu().numpy() - np.clip(ref_geo, 0, 1)).max() <= tol_of(mode)
+        assert np.abs(f32.cpu().numpy() - np.clip(ref_geo, 0, 1)).max() <= TOL
     assert st.status() == 0
     st.close()
 
@@ -115,6 +108,6 @@ def test_augmentation_argument_errors():
     o = rinr.DecodeOpts(rinr.OUT_F32, 0, None)
     o.affine = aff.data_ptr() + 2
     assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ALIGN
-    o = rinr.DecodeOpts(rinr.OUT_F32, 32, None)                     # an unknown flag bit
+    o = rinr.DecodeOpts(rinr.OUT_F32, 64, None)                     # an unknown flag bit
     assert L.rinr_decode_batch_ex(st._h, ids.data_ptr(), 2, 4, 4, out.data_ptr(), C.byref(o), None) == rinr.E_ARG
     st.close()

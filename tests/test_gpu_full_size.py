@@ -22,7 +22,10 @@ def packed_workload(k):
     return w, rinr.pack(w.models, w.w0, w.coord_lo, w.coord_hi)
 
 
-@pytest.mark.parametrize("mode", [0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT, rinr.FLAG_FP16_ALL],
+# the two reduced-precision families are forced here (the worst-case bound declines them on these deep models): what is
+# asserted is their measured error on the benchmark workloads themselves, at the same tolerance
+@pytest.mark.parametrize("mode", [0, rinr.FLAG_FP32_MFMA, rinr.FLAG_FP16_ACT | rinr.FLAG_FP16_UNCHECKED,
+                                  rinr.FLAG_FP16_ALL | rinr.FLAG_FP16_UNCHECKED],
                          ids=["split-fp16", "fp32-mfma", "fp16-act", "fp16-all"])
 @pytest.mark.parametrize("k,n_sample", [(1, 64), (2, 512), (3, 96), (4, 32), (5, 32)])
 def test_full_size_workload(k, n_sample, mode):
