@@ -227,6 +227,18 @@ int rinr_decode_batch(rinr_store *models, const int64_t *image_ids, int32_t n,
 int rinr_decode_batch_ex(rinr_store *models, const int64_t *image_ids, int32_t n,
                          int32_t H, int32_t W, void *out, const rinr_decode_opts *opts, void *stream);
 
+/* For callers that cannot allocate device memory or pass a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same as rinr_decode_batch_ex, except that the heaviest-first slot order
+ * (see rinr_decode_opts.workspace, which is ignored here) is kept in a static device array of the library instead:
+ * 4 bytes per slot, RINR_NOALLOC_MAX_SLOTS slots = 256 KB, held on every GPU the library is used on until the
+ * process ends.  n > RINR_NOALLOC_MAX_SLOTS returns RINR_E_SIZE.  The call allocates nothing and frees nothing.
+ * Every call on one GPU shares that GPU's array (whatever the store): each call rewrites the entries it reads
+ * before it reads them, so calls in sequence on one stream are independent, but calls that may overlap on
+ * one GPU (other streams, other host threads) race on it: use rinr_decode_batch_ex with a workspace of their own. */
+enum { RINR_NOALLOC_MAX_SLOTS = 65536 };
+int rinr_decode_batch_noalloc(rinr_store *models, const int64_t *image_ids, int32_t n, int32_t H, int32_t W,
+                              void *out, const rinr_decode_opts *opts, void *stream);
+
 /* Sec. III-B selects the batch on the GPU with no CPU in the loop, so an id outside the dataset can only
  * be seen by the kernel: this call synchronises `stream`, then reads (and leaves set) the count of
  * out-of-range image ids seen by decodes on this store so far. */

@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -130,6 +131,27 @@ Plan plan_chunks(double n_slots, uint32_t tiles, uint32_t nw, int n_cu, int resi
     return best;
 }
 
+// Scratch of rinr_decode_batch_noalloc: the heaviest-first slot order, 4 bytes per slot.  Every GPU the library runs
+// on holds its own copy of the array at its own address, found once per device (with that device current) when the
+// first store is opened on it.  In host code the array's name is only a stand-in for the symbol: kernels and copies
+// get the looked-up address.
+__device__ __align__(256) uint32_t scratch[RINR_NOALLOC_MAX_SLOTS];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint32_t *g_scratch_ptr[kMaxDevices];       // per device; nullptr = not looked up yet
+
+int scratch_for_device(int device, uint32_t **out) {
+    if (device < 0 || device >= kMaxDevices) return RINR_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        if (hip_fail(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) || !p) return RINR_E_HIP;
+        g_scratch_ptr[device] = (uint32_t *)p;
+    }
+    *out = g_scratch_ptr[device];
+    return RINR_OK;
+}
+
 // The three ways a model's resident size is reckoned (see resident_fits): fp32 kernels, split-precision kernels
 // with the store's own kinds of hidden layer, split-precision kernels with fp16 weights.
 enum { kSizeFp32 = 0, kSizeXdl = 1, kSizeXdl16 = 2, kSizes = 3 };
@@ -141,6 +163,7 @@ struct rinr_store {
     size_t bytes;
     StoreSummary sum;
     unsigned long long *status;
+    uint32_t *scratch;                        // this device's copy of the static scratch array
     int device;
     int n_cu;
     int tile_rows_wide;                       // fixed at open so decode and debug agree
@@ -285,6 +308,7 @@ extern "C" int rinr_store_open_ex(const void *device_blob, const void *host_blob
          allow_full_lds((const void *)decode_any_kernel<32, kThreads>);
     if (!ok) { delete s; return RINR_E_HIP; }
     if (hip_fail(hipGetDevice(&s->device))) { delete s; return RINR_E_HIP; }
+    if (int rc = scratch_for_device(s->device, &s->scratch)) { delete s; return rc; }
     hipDeviceProp_t prop;
     if (hip_fail(hipGetDeviceProperties(&prop, s->device))) { delete s; return RINR_E_HIP; }
     s->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
@@ -535,6 +559,16 @@ extern "C" int rinr_decode_batch_ex(rinr_store *s, const int64_t *image_ids, int
     s->last_info[4] = family;
     s->last_info[5] = any_streamed ? 1 : 0;
     return RINR_OK;
+}
+
+extern "C" int rinr_decode_batch_noalloc(rinr_store *s, const int64_t *image_ids, int32_t n, int32_t H, int32_t W,
+                                         void *out, const rinr_decode_opts *opts, void *stream) {
+    if (!s || !opts) return RINR_E_NULL;
+    if (n > RINR_NOALLOC_MAX_SLOTS) return RINR_E_SIZE;
+    rinr_decode_opts o = *opts;
+    o.workspace = s->scratch;                   // the device address looked up at open, never the array's name
+    o.workspace_bytes = sizeof(uint32_t) * (size_t)RINR_NOALLOC_MAX_SLOTS;
+    return rinr_decode_batch_ex(s, image_ids, n, H, W, out, &o, stream);
 }
 
 extern "C" int rinr_decode_batch(rinr_store *s, const int64_t *image_ids, int32_t n, int32_t H, int32_t W,

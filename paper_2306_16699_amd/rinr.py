@@ -27,7 +27,7 @@ FAMILIES = ("split precision (fp16 hi+lo pairs)", "fp32 MFMA", "fp16 activations
 E_NULL, E_ARG, E_MODEL, E_SIZE, E_FORMAT, E_UNSUPPORTED, E_ALIGN, E_HIP = -1, -2, -3, -4, -5, -6, -7, -8
 
 EXPORTS = ["rinr_pack_size", "rinr_pack", "rinr_unpack_layer", "rinr_store_open", "rinr_store_open_ex", "rinr_store_close",
-           "rinr_store_info", "rinr_store_error_bounds", "rinr_decode_batch", "rinr_decode_batch_ex", "rinr_store_status",
+           "rinr_store_info", "rinr_store_error_bounds", "rinr_decode_batch", "rinr_decode_batch_ex", "rinr_decode_batch_noalloc", "rinr_store_status",
            "rinr_debug_dequant", "rinr_debug_dequant_split", "rinr_last_launch_info", "rinr_strerror",
            "rinr_last_hip_error", "rinr_version", "rinr_decode_workspace_bytes"]
 
@@ -83,6 +83,7 @@ def lib():
         L.rinr_store_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32)]
         L.rinr_decode_batch.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.rinr_decode_batch_ex.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(DecodeOpts), vp]
+        L.rinr_decode_batch_noalloc.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(DecodeOpts), vp]
         L.rinr_store_status.argtypes = [vp, C.POINTER(i64), vp]
         L.rinr_debug_dequant.argtypes = [vp, i64, i32, vp, vp, vp]
         L.rinr_debug_dequant_split.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, vp]
@@ -247,14 +248,15 @@ class Store:
 
     def decode_batch_ex(self, image_ids, H: int, W: int, out_dtype: int = OUT_F32, flags: int = 0,
                         out=None, out_u8=None, stream=None, affine=None, norm=None, workspace=None,
-                        threads: int = 0, blocks_per_cu: int = 0, one_grid_min_tiles: int = 0):
+                        threads: int = 0, blocks_per_cu: int = 0, one_grid_min_tiles: int = 0, noalloc: bool = False):
         """rinr_decode_batch_ex.  Returns out (and out_u8 for OUT_F32_AND_U8).
 
         workspace: uint8 CUDA tensor of >= workspace_bytes(n) bytes (heaviest-first order for ragged stores) or None;
 
         affine: float32 CUDA tensor [n, 6] (per-slot map of the sampling grid) or None;
         norm: (scale[3], shift[3]) host numbers, sets FLAG_NORMALIZE;
-        threads, blocks_per_cu, one_grid_min_tiles: launch shape (0 = the library's choice)."""
+        threads, blocks_per_cu, one_grid_min_tiles: launch shape (0 = the library's choice);
+        noalloc: call rinr_decode_batch_noalloc (slot order in the library's static scratch) instead."""
         torch = self._torch
         n = int(image_ids.numel())
         if out is None:
@@ -274,9 +276,9 @@ class Store:
             o.flags |= FLAG_NORMALIZE
             o.norm_scale = (C.c_float * 3)(*[float(v) for v in norm[0]])
             o.norm_shift = (C.c_float * 3)(*[float(v) for v in norm[1]])
-        _check(lib().rinr_decode_batch_ex(self._h, image_ids.data_ptr() if n else None, n, H, W,
-                                          out.data_ptr() if n else None, C.byref(o), _stream_ptr(stream)),
-               "rinr_decode_batch_ex")
+        fn = lib().rinr_decode_batch_noalloc if noalloc else lib().rinr_decode_batch_ex
+        _check(fn(self._h, image_ids.data_ptr() if n else None, n, H, W, out.data_ptr() if n else None, C.byref(o),
+                  _stream_ptr(stream)), "rinr_decode_batch_noalloc" if noalloc else "rinr_decode_batch_ex")
         return (out, out_u8) if out_dtype == OUT_F32_AND_U8 else out
 
     def status(self, stream=None) -> int:
