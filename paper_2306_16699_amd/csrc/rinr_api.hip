@@ -414,6 +414,7 @@ extern "C" int rinr_decode_batch_ex(rinr_store *s, const int64_t *image_ids, int
     a.affine = opts->affine;
     a.normalize = (opts->flags & RINR_FLAG_NORMALIZE) ? 1u : 0u;
     a.tile_rows_wide = (uint32_t)s->tile_rows_wide;
+    a.vec_store = (HW % 4 == 0 && ((uintptr_t)a.out_f32 & 15) == 0 && ((uintptr_t)a.out_u8 & 3) == 0) ? 1u : 0u;
     a.lds_budget = s->lds_budget;
     for (int c = 0; c < 3; ++c) {
         a.ns[c] = a.normalize ? opts->norm_scale[c] : 1.0f;

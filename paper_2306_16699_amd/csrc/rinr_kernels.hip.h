@@ -137,12 +137,13 @@ __device__ __forceinline__ ExpandShare expand_share(const uint32_t *rec, int l0,
 }
 
 // This wavefront's part of one layer, one weight per lane.  `rec` is the model record (words; the staged copy in LDS,
-// or the record itself in global memory).  Over the
-// workgroup, put(o, i, w, q) receives every weight of the true n_out x n_in matrix exactly once: w the fp32 value
-// (0.0f where pruned) and q the integer code - zp of a coded layer (0 where pruned or for fp32 layers); putb(o, b)
-// every bias (from the wavefront that holds the layer's first block).  A kept weight's code is found by its rank
-// among the kept ones: the count before the wavefront's first block by one reduction over the mask words, then a
-// running count.
+// or the record itself in global memory).  Over the workgroup, put(o, i, w, q) receives every KEPT weight of the true
+// n_out x n_in matrix exactly once: w the fp32 value and q the integer code - zp of a coded layer (0 for fp32 layers);
+// pruned weights are not reported (the caller's area starts out as zeros); putb(o, b) receives every bias (from the
+// wavefront that holds the layer's first block).  A kept weight's code is found by its rank among the kept ones: the
+// count before the wavefront's first block by one reduction over the mask words, then, per block of 64 weights, the
+// block's keep bits as one 64-bit lane mask (a ballot), the lane's rank by a masked bit count, and the running count in
+// a scalar register.
 template <class PutW, class PutB>
 __device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec &r, int lane, ExpandShare &sh, PutW put, PutB putb) {
     const uint32_t n_in = r.n_in, cnt = (uint32_t)r.n_in * r.n_out;
@@ -155,35 +156,41 @@ __device__ __forceinline__ void expand_layer(const uint32_t *rec, const LayerRec
     const uint32_t *cs = rec + (r.code_off >> 2);
     const uint32_t cb = r.bits ? r.bits : 32u;
     const uint32_t magic = n_in > 1 ? 0xFFFFFFFFu / n_in + 1u : 0u;     // ceil(2^32 / n_in): k / n_in == umulhi(k, magic) for k < 2^16
-    auto mask_word = [&](uint32_t wi) -> uint32_t {
-        if (wi >= nwords) return 0u;
-        if (r.has_mask) return mw[wi];
-        return (wi == nwords - 1 && (cnt & 31)) ? (1u << (cnt & 31)) - 1u : 0xFFFFFFFFu;
-    };
+    const bool has_mask = r.has_mask != 0;
     uint32_t running = 0;
     if (b0) {
-        uint32_t part = 0;
-        for (uint32_t wi = lane; wi < 2 * b0; wi += 64) part += __popc(mask_word(wi));
-        running = wave_sum(part);
+        if (has_mask) {
+            uint32_t part = 0;
+            for (uint32_t wi = lane; wi < 2 * b0; wi += 64) part += __popc(wi < nwords ? mw[wi] : 0u);
+            running = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_sum(part));
+        } else {
+            running = b0 << 6;          // dense: every weight before the block is kept (b0 < nblocks, so all of them exist)
+        }
     }
     for (uint32_t b = b0; b < b1; ++b) {
-        const uint32_t k = (b << 6) + (uint32_t)lane, bit = (uint32_t)lane & 31u;
-        const uint32_t m = mask_word(k >> 5);
-        const uint32_t pc = __popc(m);
-        const uint32_t pc_lo = __shfl(pc, 0, 64), pc_hi = __shfl(pc, 32, 64);
-        if (k < cnt) {
+        const uint32_t k = (b << 6) + (uint32_t)lane;
+        bool kept = k < cnt;
+        if (has_mask) {
+            const uint32_t wi = k >> 5;
+            const uint32_t word = wi < nwords ? mw[wi] : 0u;      // bits past the layer's end are zero in a valid record
+            kept = (word >> ((uint32_t)lane & 31u)) & 1u;
+        }
+        const uint64_t keep64 = __ballot(kept);
+        const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(keep64 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)keep64, running));
+        running += (uint32_t)__popcll(keep64);
+        if (kept) {
+            uint32_t code;
+            if (cb == 8u) code = ((const uint8_t *)cs)[rank];
+            else if (cb == 32u) code = cs[rank];
+            else if (cb == 16u) code = ((const uint16_t *)cs)[rank];
+            else code = take_code(cs, rank, cb);
             const uint32_t o = n_in == 1 ? k : __umulhi(k, magic), i = k - o * n_in;
-            float val = 0.0f;
+            float val;
             int32_t q = 0;
-            if ((m >> bit) & 1u) {
-                const uint32_t rank = running + (lane >= 32 ? pc_lo : 0u) + __popc(m & ((1u << bit) - 1u));
-                const uint32_t code = take_code(cs, rank, cb);
-                if (r.bits) { q = (int32_t)code - r.zp; val = r.scale * (float)q; }
-                else val = __uint_as_float(code);
-            }
+            if (r.bits) { q = (int32_t)code - r.zp; val = r.scale * (float)q; }
+            else val = __uint_as_float(code);
             put((int)o, (int)i, val, q);
         }
-        running += pc_lo + pc_hi;
     }
     if (b0 == 0) {
         const float *bias = (const float *)(rec + (r.bias_off >> 2));
@@ -276,6 +283,8 @@ struct DecodeArgs {
     float ns[3], nb[3];           // per-channel scale / shift applied after the clamp when normalize != 0
     uint32_t normalize;
     const uint32_t *order;        // workgroups take the slots in this order (heaviest model first), or NULL = 0, 1, 2, ...
+    uint32_t vec_store;           // H * W is a multiple of 4, the fp32 output 16-byte and the uint8 output 4-byte aligned:
+                                  // a lane's consecutive pixels go out as one vector
 };
 
 // sin(2 pi r): the hardware sine takes its argument in revolutions and reduces the range

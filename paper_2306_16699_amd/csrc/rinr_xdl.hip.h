@@ -15,7 +15,16 @@
 // all row tiles of the layer) holds rows
 //     TM = 16:  16 Q + 4 g + b            TM = 32:  32 (Q / 4) + 8 (Q % 4) + 4 g + b,   b = 0..3.
 // One MFMA k-step takes 8 halfs per lane = quads 2j and 2j+1 of every lane group, i.e. exactly the
-// activations the lanes already hold, so again nothing crosses lanes between layers.
+// activations the lanes already hold, so again nothing crosses lanes between layers.  An odd last quad (padded widths
+// 16 and 48) takes a half-depth step, v_mfma_f32_16x16x16_f16, on the same accumulators.
+// Two MFMAs of different depth must not follow each other closely on one accumulator: with a 16x16x16 step issued
+// right behind a 16x16x32 step that writes its C operand (one vector instruction between them, no wait states
+// added by the compiler) the second read the accumulator before the first had written it, and the first step's
+// contribution was lost.  So all full-depth steps of a layer are issued first, then 20 idle cycles of this wavefront
+// (one more than the longest wait the instruction set documents between dependent matrix instructions of different
+// kinds; the SIMD's other wavefronts issue meanwhile), then all half-depth steps,
+// the order being forced through the accumulators themselves (xdl_touch).  tests/test_gpu_parity.py pins it with a
+// model whose output must contain a term that only the full-depth step supplies.
 #pragma once
 #include "rinr_kernels.hip.h"
 
@@ -249,6 +258,13 @@ __device__ __forceinline__ void sine_hi(float d0, float d1, float d2, float d3, 
     hi = (h4v){a0[0], a0[1], a1[0], a1[1]};
 }
 
+// Between the full-depth and the half-depth MFMAs of one set of accumulators: 20 wait states that no MFMA of the set
+// can cross.  The empty asm statements make every accumulator an operand: the full-depth steps that produce it must
+// come before the first, the half-depth steps that consume it after the last, and volatile asm statements keep their
+// order, so the idle cycles sit between the two groups whatever the scheduler does with the rest.
+template <class Acc> __device__ __forceinline__ void xdl_touch(Acc &acc) { asm volatile("" : "+v"(acc)); }
+__device__ __forceinline__ void xdl_wait_states() { asm volatile("s_nop 15\n\ts_nop 3"); }
+
 // ---- per-wavefront state of one half (32 pixels) of a 64-pixel tile ------------------------------------
 template <int TM, int WP> struct XHalf {
     typedef XLayout<TM, WP> LY;
@@ -321,6 +337,17 @@ __device__ __forceinline__ void xdl_hidden(XHalf<TM, WP> &H, const char *lds, co
             }
         }
     if (K16) {
+        if (KJ) {
+#pragma unroll
+            for (int nt = 0; nt < NTH; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) xdl_touch(H.D[nt][mt]);
+            xdl_wait_states();
+#pragma unroll
+            for (int nt = 0; nt < NTH; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) xdl_touch(H.D[nt][mt]);
+        }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const h4v av = ah4[mt * 64];
@@ -369,7 +396,7 @@ __device__ __forceinline__ XUniform xdl_uniform(const DecodeArgs &a, uint32_t sl
     return u;
 }
 
-// ---- first layer: every lane forms the coordinates of its own pixel (tile * 64 + lane) as hi/lo halfs in
+// ---- first layer: every lane forms the coordinates of one pixel of the tile as hi/lo halfs in
 //      k slots (xh, yh, xl, yl, xh, yh, 0, 0); the MFMA of pixel tile q uses the weight variant whose
 //      non-zero k slots are lane group q's, so one operand register set serves all pixel tiles.
 //      Per-lane values that only the first and the last layer use are derived again for every tile
@@ -387,7 +414,9 @@ __device__ __forceinline__ void xdl_first(XHalf<TM, WP> &X, XHalf<TM, WP> &Y, co
     asm volatile("" : "+s"(lo_v), "+s"(af2), "+s"(af5));
     const h8v *a0 = (const h8v *)(lds + e0.off_hi) + lane;
     const acc_t *bt = (const acc_t *)(lds + e0.off_bias) + g;
-    uint32_t p = (tile << 6) + (uint32_t)lane;
+    // lane (pixel tile q = lane / TM, column n = lane % TM) feeds pixel n * (64 / TM) + q of the 64: a lane's columns of the
+    // pixel tiles are then consecutive pixels, which the output layer stores as one vector
+    uint32_t p = (tile << 6) + (uint32_t)(lane % TM) * (64 / TM) + (uint32_t)(lane / TM);
     p = min(p, a.HW - 1);
     const uint32_t row = a.wmagic ? (__umulhi(p, a.wmagic) >> a.wshift) : p, col = p - row * a.W;
     const float x0 = fmaf(a.span, (float)(2 * col + 1) * a.inv2W, lo_v);
@@ -440,6 +469,13 @@ __device__ __forceinline__ void xdl_output(const XHalf<TM, WP> &X, const XHalf<T
         }
     }
     if (K16) {
+        if (KJ) {
+#pragma unroll
+            for (int nt = 0; nt < 2 * NTH; ++nt) xdl_touch(O[nt]);
+            xdl_wait_states();
+#pragma unroll
+            for (int nt = 0; nt < 2 * NTH; ++nt) xdl_touch(O[nt]);
+        }
         const h4v av = ah4[0], aw = al4[0];
 #pragma unroll
         for (int nt = 0; nt < 2 * NTH; ++nt) {
@@ -449,22 +485,45 @@ __device__ __forceinline__ void xdl_output(const XHalf<TM, WP> &X, const XHalf<T
             O[nt] = T::mfma_half(aw, bh, O[nt]);
         }
     }
+    // lane (go, no) holds column `no` of every pixel tile: pixels p0 .. p0 + NT - 1 of the image, NT = 64 / TM
+    constexpr int NT = 2 * NTH;
+    constexpr int NS = TM == 16 ? 1 : 2;         // channels a lane stores: TM = 16: channel go; TM = 32: R and B (group 0), G (group 1)
+    const uint32_t p0 = (tile << 6) + (uint32_t)no * NT;
 #pragma unroll
-    for (int nt = 0; nt < 2 * NTH; ++nt) {
-        const uint32_t p = (tile << 6) + nt * TM + no;
-        constexpr int NS = TM == 16 ? 1 : 2;     // values a lane may store per pixel tile
+    for (int k = 0; k < NS; ++k) {
+        const int ch = TM == 16 ? go : (go == 0 ? 2 * k : 1);
+        const bool live = TM == 16 ? go < 3 : (go == 0 || k == 0);
+        float r[NT];
 #pragma unroll
-        for (int k = 0; k < NS; ++k) {
-            const int ch = TM == 16 ? go : (go == 0 ? 2 * k : 1);
-            const bool live = TM == 16 ? go < 3 : (go == 0 || k == 0);
-            float r = O[nt][TM == 16 ? 0 : 4 * k];
-            if (!a.no_clamp) r = fminf(fmaxf(r, 0.0f), 1.0f);
-            if (a.normalize) r = fmaf(r, ch == 0 ? ns0 : (ch == 1 ? ns1 : ns2), ch == 0 ? nb0 : (ch == 1 ? nb1 : nb2));
-            if (live && p < a.HW) {
-                const uint32_t at = (uint32_t)ch * a.HW + p;  // within the slot's three planes: 3 HW < 2^32 is checked by the host
-                if (a.out_f32) (a.out_f32 + plane0)[at] = r;
-                if (a.out_u8) (a.out_u8 + plane0)[at] = (uint8_t)rintf(255.0f * r);
+        for (int nt = 0; nt < NT; ++nt) {
+            r[nt] = O[nt][TM == 16 ? 0 : 4 * k];
+            if (!a.no_clamp) r[nt] = fminf(fmaxf(r[nt], 0.0f), 1.0f);
+            if (a.normalize) r[nt] = fmaf(r[nt], ch == 0 ? ns0 : (ch == 1 ? ns1 : ns2), ch == 0 ? nb0 : (ch == 1 ? nb1 : nb2));
+        }
+        const uint32_t at = (uint32_t)ch * a.HW + p0;       // within the slot's three planes: 3 HW < 2^32 is checked by the host
+        if (a.vec_store) {                                  // HW is a multiple of 4 and the outputs are aligned: whole vectors
+            if (live && p0 < a.HW) {
+                if (a.out_f32) {
+                    float *dst = a.out_f32 + plane0 + at;
+                    if constexpr (NT == 4) *(f32x4 *)dst = (f32x4){r[0], r[1], r[2], r[3]};
+                    else *(f2v *)dst = (f2v){r[0], r[1]};
+                }
+                if (a.out_u8) {
+                    uint32_t pk = 0u;
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) pk = __builtin_amdgcn_cvt_pk_u8_f32(255.0f * r[nt], nt, pk);   // round to nearest even, packed
+                    uint8_t *dst = a.out_u8 + plane0 + at;
+                    if constexpr (NT == 4) *(uint32_t *)dst = pk;
+                    else *(uint16_t *)dst = (uint16_t)pk;
+                }
             }
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (live && p0 + nt < a.HW) {
+                    if (a.out_f32) (a.out_f32 + plane0)[at + nt] = r[nt];
+                    if (a.out_u8) (a.out_u8 + plane0)[at + nt] = (uint8_t)rintf(255.0f * r[nt]);
+                }
         }
     }
 }
