@@ -75,8 +75,14 @@ typedef struct rinr_fit rinr_fit;
 /* Device state for fitting n_images models of one architecture to H x W targets: parameters,
  * Adam moments, keep flags and per-image losses (3 * 4 + 1 bytes per parameter).  All images share
  * the architecture; each has its own parameters.  RINR_E_ARG for a bad architecture or size,
- * RINR_E_UNSUPPORTED if the model is deeper than the kernels are built for (widest hidden layer <= 32: 12 linear
- * layers, <= 48: 10, <= 64: 7; the weights of all layers stay in one CU's LDS and the gradients in registers), RINR_E_HIP. */
+ * RINR_E_UNSUPPORTED if the model is deeper than the kernels are built for: widest hidden layer <= 32: 12 linear
+ * layers, <= 48: 10, <= 64: 7.  These limits are narrower than the decode side's (16 layers of width 64, deep models
+ * streamed) for a reason of the fit kernel's design: one Adam step keeps the fp32 weights of all layers in one CU's
+ * LDS (10 layers x 40: 148 KB, 7 layers x 64: 155 KB of the 160) and the weight-gradient tiles of all layers in the
+ * owning wavefronts' registers from the first pixel to the update, so gradients never touch memory; a deeper model
+ * at these widths fits neither.  The paper's own shapes (Sec. VI-A: 3 x 15, 10 x 32, 10 x 40) and the benchmark's
+ * widest model (7 layers x 64) fit; a model beyond the limits can still be packed and decoded, only not fitted here.
+ * RINR_E_HIP on a failed allocation. */
 int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, rinr_fit **fit);
 int rinr_fit_destroy(rinr_fit *fit);
 int64_t rinr_fit_n_params(const rinr_fit *fit);        /* per image; < 0 on NULL */

@@ -139,7 +139,7 @@ __device__ __forceinline__ void xdl_expand_layers(char *lds, const uint32_t *rec
                                                   int nthreads, uint32_t zero_bytes) {
     typedef XLayout<TM, WP> LY;
     XLayer *tab = (XLayer *)lds;
-    for (uint32_t q = tid; q < (zero_bytes >> 2); q += nthreads) ((uint32_t *)lds)[q] = 0u;
+    for (uint32_t q = tid; q < (zero_bytes >> 4); q += nthreads) ((uint4 *)lds)[q] = make_uint4(0u, 0u, 0u, 0u);   // zero_bytes is a multiple of 16
     __syncthreads();
     if (tid == 0) {
         uint32_t bias = LY::TABLE;
