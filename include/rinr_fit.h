@@ -72,18 +72,30 @@ typedef struct {
 
 typedef struct rinr_fit rinr_fit;
 
-/* Device state for fitting n_images models of one architecture to H x W targets: parameters,
- * Adam moments, keep flags and per-image losses (3 * 4 + 1 bytes per parameter).  All images share
- * the architecture; each has its own parameters.  RINR_E_ARG for a bad architecture or size,
- * RINR_E_UNSUPPORTED if the model is deeper than the kernels are built for: widest hidden layer <= 32: 12 linear
- * layers, <= 48: 10, <= 64: 7.  These limits are narrower than the decode side's (16 layers of width 64, deep models
- * streamed) for a reason of the fit kernel's design: one Adam step keeps the fp32 weights of all layers in one CU's
- * LDS (10 layers x 40: 148 KB, 7 layers x 64: 155 KB of the 160) and the weight-gradient tiles of all layers in the
- * owning wavefronts' registers from the first pixel to the update, so gradients never touch memory; a deeper model
- * at these widths fits neither.  The paper's own shapes (Sec. VI-A: 3 x 15, 10 x 32, 10 x 40) and the benchmark's
- * widest model (7 layers x 64) fit; a model beyond the limits can still be packed and decoded, only not fitted here.
- * RINR_E_HIP on a failed allocation. */
+enum { RINR_FIT_FLAG_FP32_MFMA = 1 };   /* rinr_fit_create_ex: take the fp32 matrix-instruction kernels whatever the shape */
+enum { RINR_FIT_KERNEL_FP32 = 0,        /* rinr_fit_kernel_family: fp32 operands on the fp32 matrix instructions              */
+       RINR_FIT_KERNEL_SPLIT16 = 1 };   /* every fp32 operand as an exact-sum pair of halfs on the fp16 matrix instructions,
+                                           three terms per product, fp32 accumulate (~22 significant bits per product)       */
+
+/* Device state for fitting n_images models of one architecture to H x W targets (Eq. 1): parameters, Adam moments, keep
+ * flags, per-image losses (3 * 4 + 1 bytes per parameter).  All images share the architecture; each has its own parameters.
+ * Two families of kernels compute the same step.  The split-precision ones (the default where they are built for the
+ * shape) keep the weights of all layers in one CU's LDS as fp16 hi/lo planes and the pre-activations of 16 pixels per
+ * wavefront in registers: widest hidden layer <= 32: 12 linear layers, <= 48: 10, <= 64: 6.  The fp32 ones keep fp32 weights
+ * in LDS: <= 32: 12 layers, <= 48: 10, <= 64: 7.  A shape only the fp32 kernels cover (7 layers x 64) takes those;
+ * RINR_E_UNSUPPORTED beyond both.  These limits are narrower than the decode side's (16 layers of width 64, deep models
+ * streamed) for a reason of the fit kernels' design: one Adam step keeps the weights of all layers in LDS (10 layers x 40:
+ * 148 KB, 7 layers x 64: 155 KB of the 160) and the weight-gradient tiles of all layers in the owning wavefronts' registers
+ * from the first pixel to the update, so gradients never touch memory; a deeper model at these widths fits neither.  The
+ * paper's own shapes (Sec. VI-A: 3 x 15, 10 x 32, 10 x 40) and the benchmark's widest model (7 layers x 64) fit; a model
+ * beyond the limits can still be packed and decoded, only not fitted here.
+ * flags: 0 or RINR_FIT_FLAG_FP32_MFMA.  RINR_E_ARG for a bad architecture, size or flag; RINR_E_HIP on a failed allocation.
+ * rinr_fit_create == rinr_fit_create_ex with flags = 0. */
 int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, rinr_fit **fit);
+int rinr_fit_create_ex(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, uint32_t flags, rinr_fit **fit);
+/* Which kernels this handle's steps run: RINR_FIT_KERNEL_*; RINR_E_NULL on NULL.  (Sec. VI-A fixes the method, not the
+ * arithmetic; both families meet the same parity bar against the fp64 reference.) */
+int rinr_fit_kernel_family(const rinr_fit *fit);
 int rinr_fit_destroy(rinr_fit *fit);
 int64_t rinr_fit_n_params(const rinr_fit *fit);        /* per image; < 0 on NULL */
 

@@ -106,6 +106,7 @@ struct FitArgs {
     const uint8_t *keep;          // [n_images][n_params] or null
     const float *target;          // [n_images][3][HW]
     float *loss;                  // [n_images]
+    float *emag;                  // [n_images] root-mean-square output error the last step saw (split-precision kernel's error scale); may be null
     float *grad_out;              // null: Adam update; else the gradient is written here and nothing is updated
     int64_t n_params;
     uint32_t HW, W;
@@ -142,6 +143,10 @@ __device__ __forceinline__ f32x4 contract(const float *ap, const float *bp, f32x
     }
     return acc;
 }
+
+}  // namespace
+#include "rinr_fit16.hip.h"
+namespace {
 
 // Where entry (o, i) of layer l's weight-gradient tile lives in the parameter vector, or -1 (padding).
 // Column 0 is the bias; input j is column 1 + j of the first layer and column 4 + j of the others.
@@ -411,13 +416,44 @@ int lds_floats(int wq, int L) {
     }
 }
 
+
+// ---- the split-precision kernels (rinr_fit16.hip.h): built per hidden width rounded up to a multiple of 16 and per depth bucket
+constexpr int fit16_depth_lo(int wp) { return wp == 16 ? 4 : 6; }
+constexpr int fit16_depth_hi(int wp) { return wp <= 32 ? kMaxL : (wp == 48 ? 10 : 6); }
+template <int WP> fit_fn kernel16_of(int L) {
+    if (L <= fit16_depth_lo(WP)) return fit16::fit16_step_kernel<WP, fit16_depth_lo(WP)>;
+    return fit16::fit16_step_kernel<WP, fit16_depth_hi(WP)>;
+}
+fit_fn kernel16_for(int wp, int L) {
+    switch (wp) {
+        case 16: return kernel16_of<16>(L);
+        case 32: return kernel16_of<32>(L);
+        case 48: return kernel16_of<48>(L);
+        default: return kernel16_of<64>(L);
+    }
+}
+// LDS bytes of a model of L linear layers at padded width wp, or 0 if no split kernel is built that deep
+uint32_t lds_bytes16(int wp, int L) {
+    if (L > fit16_depth_hi(wp)) return 0;
+    switch (wp) {
+        case 16: return fit16::Shape<16>::total(L);
+        case 32: return fit16::Shape<32>::total(L);
+        case 48: return fit16::Shape<48>::total(L);
+        default: return fit16::Shape<64>::total(L);
+    }
+}
+
 }  // namespace
 
 struct rinr_fit {
     rinr_fit_arch arch;
     int64_t n_images, n_params;
     int32_t H, W;
-    int wq, lds_floats;         // wq: widest hidden layer rounded up to a multiple of 8
+    int wq, lds_floats;         // wq: widest hidden layer rounded up to a multiple of 8 (fp32 kernels); lds_floats 0 = no fp32 kernel fits
+    int family;                 // RINR_FIT_KERNEL_FP32 or RINR_FIT_KERNEL_SPLIT16: the kernels this handle's steps run
+    int wp;                     // widest hidden layer rounded up to a multiple of 16 (split kernels)
+    uint32_t lds16;             // their LDS bytes
+    float *emag;                // [n_images] error size seen by the last step (split kernels' error scale); 0 = none yet
     int32_t p_off[kMaxL];
     float *params, *m, *v, *loss, *scratch_grad;
     uint8_t *keep;            // null until set
@@ -425,10 +461,11 @@ struct rinr_fit {
     int64_t t;                // Adam steps taken
 };
 
-extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, rinr_fit **out) {
+extern "C" int rinr_fit_create_ex(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, uint32_t flags, rinr_fit **out) {
     if (!arch || !out) return RINR_E_NULL;
     *out = nullptr;
     if (arch->n_layers < 2 || arch->n_layers > kMaxL || n_images < 0 || H <= 0 || W <= 0) return RINR_E_ARG;
+    if (flags & ~(uint32_t)RINR_FIT_FLAG_FP32_MFMA) return RINR_E_ARG;
     if ((int64_t)H * W >= ((int64_t)1 << 31) || n_images > ((int64_t)1 << 31) - 1) return RINR_E_SIZE;
     if (arch->widths[0] != 2 || arch->widths[arch->n_layers] != 3) return RINR_E_ARG;
     for (int l = 1; l < arch->n_layers; ++l)
@@ -445,31 +482,45 @@ extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int3
     int wmax = 1;
     for (int l = 1; l < arch->n_layers; ++l) wmax = arch->widths[l] > wmax ? arch->widths[l] : wmax;
     f->wq = (wmax + 7) / 8 * 8;
+    f->wp = (wmax + 15) / 16 * 16;
     f->lds_floats = lds_floats(f->wq, arch->n_layers);
-    if (f->lds_floats == 0 || (size_t)f->lds_floats * 4 + 256 > kLdsLimit) { delete f; return RINR_E_UNSUPPORTED; }
+    if ((size_t)f->lds_floats * 4 + 256 > kLdsLimit) f->lds_floats = 0;
+    f->lds16 = lds_bytes16(f->wp, arch->n_layers);
+    if ((size_t)f->lds16 + 256 > kLdsLimit) f->lds16 = 0;
+    // the split-precision kernels where they are built for the shape, the fp32 ones otherwise or on request
+    f->family = (f->lds16 && !(flags & RINR_FIT_FLAG_FP32_MFMA)) ? RINR_FIT_KERNEL_SPLIT16 : RINR_FIT_KERNEL_FP32;
+    if (f->family == RINR_FIT_KERNEL_FP32 && f->lds_floats == 0) { delete f; return RINR_E_UNSUPPORTED; }
     f->n_params = 0;
     for (int l = 0; l < arch->n_layers; ++l) {
         f->p_off[l] = (int32_t)f->n_params;
         f->n_params += (int64_t)arch->widths[l + 1] * (arch->widths[l] + 1);
     }
-    const size_t np = (size_t)(n_images > 0 ? n_images : 1) * (size_t)f->n_params;
-    f->params = f->m = f->v = f->loss = f->scratch_grad = nullptr;
+    const size_t ni = (size_t)(n_images > 0 ? n_images : 1);
+    const size_t np = ni * (size_t)f->n_params;
+    f->params = f->m = f->v = f->loss = f->scratch_grad = f->emag = nullptr;
     f->keep = nullptr;
     f->has_keep = false;
     f->t = 0;
+    const void *fn = f->family == RINR_FIT_KERNEL_SPLIT16 ? (const void *)kernel16_for(f->wp, arch->n_layers)
+                                                         : (const void *)kernel_for(f->wq, arch->n_layers);
     if (hip_fail(hipMalloc((void **)&f->params, np * 4)) || hip_fail(hipMalloc((void **)&f->m, np * 4)) ||
         hip_fail(hipMalloc((void **)&f->v, np * 4)) || hip_fail(hipMalloc((void **)&f->keep, np)) ||
-        hip_fail(hipMalloc((void **)&f->loss, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
+        hip_fail(hipMalloc((void **)&f->loss, ni * 4)) || hip_fail(hipMalloc((void **)&f->emag, ni * 4)) ||
         hip_fail(hipMemset(f->params, 0, np * 4)) || hip_fail(hipMemset(f->m, 0, np * 4)) ||
-        hip_fail(hipMemset(f->v, 0, np * 4)) || hip_fail(hipMemset(f->loss, 0, (size_t)(n_images > 0 ? n_images : 1) * 4)) ||
-        hip_fail(hipFuncSetAttribute((const void *)kernel_for(f->wq, arch->n_layers), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)kLdsLimit - 256))) {
+        hip_fail(hipMemset(f->v, 0, np * 4)) || hip_fail(hipMemset(f->loss, 0, ni * 4)) || hip_fail(hipMemset(f->emag, 0, ni * 4)) ||
+        hip_fail(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit - 256))) {
         rinr_fit_destroy(f);
         return RINR_E_HIP;
     }
     *out = f;
     return RINR_OK;
 }
+
+extern "C" int rinr_fit_create(const rinr_fit_arch *arch, int64_t n_images, int32_t H, int32_t W, rinr_fit **out) {
+    return rinr_fit_create_ex(arch, n_images, H, W, 0u, out);
+}
+
+extern "C" int rinr_fit_kernel_family(const rinr_fit *f) { return f ? f->family : RINR_E_NULL; }
 
 extern "C" int rinr_fit_destroy(rinr_fit *f) {
     if (!f) return RINR_OK;
@@ -479,6 +530,7 @@ extern "C" int rinr_fit_destroy(rinr_fit *f) {
     (void)hipFree(f->keep);
     (void)hipFree(f->loss);
     (void)hipFree(f->scratch_grad);
+    (void)hipFree(f->emag);
     delete f;
     return RINR_OK;
 }
@@ -508,6 +560,7 @@ extern "C" int rinr_fit_reset_optimizer(rinr_fit *f) {
         FIT_HIP(hipMemset(f->m, 0, np * 4));
         FIT_HIP(hipMemset(f->v, 0, np * 4));
     }
+    if (f->n_images) FIT_HIP(hipMemset(f->emag, 0, (size_t)f->n_images * 4));      // a new round: no error history
     f->t = 0;
     return RINR_OK;
 }
@@ -532,6 +585,7 @@ extern "C" int rinr_fit_set_keep(rinr_fit *f, const uint8_t *keep) {
     if (!f) return RINR_E_NULL;
     const size_t np = (size_t)f->n_images * (size_t)f->n_params;
     FIT_HIP(hipDeviceSynchronize());
+    if (f->n_images) FIT_HIP(hipMemset(f->emag, 0, (size_t)f->n_images * 4));
     if (!keep) { f->has_keep = false; return RINR_OK; }
     if (np) FIT_HIP(hipMemcpy(f->keep, keep, np, hipMemcpyHostToDevice));
     f->has_keep = true;
@@ -554,6 +608,7 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.keep = f->has_keep ? f->keep : nullptr;
     a.target = targets;
     a.loss = f->loss;
+    a.emag = f->emag;
     a.grad_out = grad_out;
     a.n_params = f->n_params;
     a.HW = (uint32_t)(f->H * f->W);
@@ -579,7 +634,10 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.L = f->arch.n_layers;
     for (int l = 0; l <= a.L; ++l) a.d[l] = f->arch.widths[l];
     for (int l = 0; l < a.L; ++l) a.p_off[l] = f->p_off[l];
-    hipLaunchKernelGGL(kernel_for(f->wq, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->wq)), (size_t)f->lds_floats * 4, stream, a);
+    if (f->family == RINR_FIT_KERNEL_SPLIT16)
+        hipLaunchKernelGGL(kernel16_for(f->wp, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit16::fit16_waves(f->wp)), (size_t)f->lds16, stream, a);
+    else
+        hipLaunchKernelGGL(kernel_for(f->wq, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->wq)), (size_t)f->lds_floats * 4, stream, a);
     FIT_HIP(hipGetLastError());
     return RINR_OK;
 }

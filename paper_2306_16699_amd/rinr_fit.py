@@ -14,7 +14,10 @@ from . import rinr
 from .synth import Layer, Model
 
 MAX_LAYERS = 12
-EXPORTS = ["rinr_prune_ratio", "rinr_l1_mask", "rinr_quantize_layer", "rinr_fit_create", "rinr_fit_destroy",
+FIT_FLAG_FP32_MFMA = 1
+KERNEL_FP32, KERNEL_SPLIT16 = 0, 1
+EXPORTS = ["rinr_prune_ratio", "rinr_l1_mask", "rinr_quantize_layer", "rinr_fit_create", "rinr_fit_create_ex", "rinr_fit_kernel_family",
+           "rinr_fit_destroy",
            "rinr_fit_n_params", "rinr_fit_set_params", "rinr_fit_set_keep", "rinr_fit_reset_optimizer",
            "rinr_fit_get_params", "rinr_fit_steps", "rinr_fit_loss_grad", "rinr_fit_last_loss", "rinr_psnr_batch", "rinr_encode_blob_bound",
            "rinr_encode_images"]
@@ -48,6 +51,8 @@ def lib():
         L.rinr_l1_mask.argtypes = [vp, i64, dbl, vp, vp]
         L.rinr_quantize_layer.argtypes = [vp, vp, i64, i32, C.POINTER(C.c_float), C.POINTER(i32), vp]
         L.rinr_fit_create.argtypes = [C.POINTER(FitArch), i64, i32, i32, C.POINTER(vp)]
+        L.rinr_fit_create_ex.argtypes = [C.POINTER(FitArch), i64, i32, i32, C.c_uint32, C.POINTER(vp)]
+        L.rinr_fit_kernel_family.argtypes = [vp]
         L.rinr_fit_destroy.argtypes = [vp]
         L.rinr_fit_n_params.argtypes = [vp]
         L.rinr_fit_n_params.restype = i64
@@ -106,7 +111,7 @@ class Fit:
     """Device state for fitting n_images models of one architecture (widths = [2, ..., 3])."""
 
     def __init__(self, widths: Sequence[int], n_images: int, H: int, W: int, w0: float = 30.0,
-                 coord_lo: float = -1.0, coord_hi: float = 1.0):
+                 coord_lo: float = -1.0, coord_hi: float = 1.0, fp32: bool = False):
         self.widths = [int(x) for x in widths]
         if len(self.widths) - 1 > MAX_LAYERS:
             raise rinr.RinrError(rinr.E_ARG, "rinr_fit_create")
@@ -118,8 +123,10 @@ class Fit:
         self.w0, self.coord_lo, self.coord_hi = w0, coord_lo, coord_hi
         self.n_images, self.H, self.W = n_images, H, W
         h = C.c_void_p()
-        rinr._check(lib().rinr_fit_create(C.byref(arch), n_images, H, W, C.byref(h)), "rinr_fit_create")
+        rinr._check(lib().rinr_fit_create_ex(C.byref(arch), n_images, H, W, FIT_FLAG_FP32_MFMA if fp32 else 0, C.byref(h)),
+                    "rinr_fit_create_ex")
         self._h = h
+        self.kernel_family = int(lib().rinr_fit_kernel_family(h))      # KERNEL_FP32 or KERNEL_SPLIT16
         self.n_params = int(lib().rinr_fit_n_params(h))
 
     def close(self):

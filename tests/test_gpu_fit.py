@@ -37,9 +37,13 @@ def keep_flags(rng, widths, n, prob):
     return np.stack(ks)
 
 
+FAMILIES = {"split16": False, "fp32": True}      # the two kernel families of rinr_fit_create_ex, each held to the same bars
+
+
+@pytest.mark.parametrize("family", list(FAMILIES))
 @pytest.mark.parametrize("name", list(ARCHS))
 @pytest.mark.parametrize("masked", [False, True])
-def test_loss_and_gradient(name, masked):
+def test_loss_and_gradient(name, masked, family):
     widths, H, W = ARCHS[name]
     n = 3
     rng = np.random.default_rng(len(name))
@@ -47,7 +51,10 @@ def test_loss_and_gradient(name, masked):
     tgt, tgt_d = targets_of(11, n, H, W)
     keep = keep_flags(rng, widths, n, 0.6) if masked else None
     lo, hi = (0.0, 1.0) if "tapered" in name else (-1.0, 1.0)
-    f = rinr_fit.Fit(widths, n, H, W, coord_lo=lo, coord_hi=hi)
+    f = rinr_fit.Fit(widths, n, H, W, coord_lo=lo, coord_hi=hi, fp32=FAMILIES[family])
+    # the split-precision kernels serve every shape here but 7 layers x 64, which only the fp32 kernels hold
+    want_family = rinr_fit.KERNEL_FP32 if (FAMILIES[family] or name == "width 64 x6") else rinr_fit.KERNEL_SPLIT16
+    assert f.kernel_family == want_family
     if keep is not None:
         f.set_keep(keep)
     f.set_params(p0)
@@ -72,15 +79,16 @@ def test_loss_and_gradient(name, masked):
     f.close()
 
 
+@pytest.mark.parametrize("family", list(FAMILIES))
 @pytest.mark.parametrize("name", ["cifar 3x15 @32x32", "mini-imagenet 10x40 ragged", "tapered"])
-def test_adam_steps_follow_the_oracle(name):
+def test_adam_steps_follow_the_oracle(name, family):
     widths, H, W = ARCHS[name]
     n, steps, lr, T = 2, 4, 5e-4, 10
     rng = np.random.default_rng(3)
     p0 = synth.init_params(5, widths, n)
     tgt, tgt_d = targets_of(13, n, H, W)
     keep = keep_flags(rng, widths, n, 0.8)
-    f = rinr_fit.Fit(widths, n, H, W)
+    f = rinr_fit.Fit(widths, n, H, W, fp32=FAMILIES[family])
     f.set_keep(keep)
     f.set_params(p0)
     losses = []
@@ -101,6 +109,39 @@ def test_adam_steps_follow_the_oracle(name):
     f.set_params(p0)
     f.steps(tgt_d, steps, lr, t0=0, T=T)
     np.testing.assert_array_equal(f.get_params(), got)
+    f.close()
+
+
+def test_split_kernels_carry_the_error_at_any_size():
+    """The split-precision kernels carry the back-propagated error in fp16 times a power of two chosen from the size of
+    the error (the last step's, once there is one) and from the weights' gains.  Parity of the gradient must not depend on
+    that size: loss scales from 1e-9 to 1e3, targets far off the prediction, and the state after some steps, when the
+    scale comes from the steps' own history."""
+    widths, H, W, n = [2, 24, 40, 24, 3], 12, 10, 2
+    p0 = synth.init_params(31, widths, n)
+    tgt, tgt_d = targets_of(37, n, H, W)
+    f = rinr_fit.Fit(widths, n, H, W)
+    assert f.kernel_family == rinr_fit.KERNEL_SPLIT16
+    f.set_params(p0)
+
+    def check(targets, targets_d, params, loss_scale):
+        loss, grad = f.loss_grad(targets_d, loss_scale=loss_scale)
+        assert np.isfinite(grad).all() and np.isfinite(loss).all()
+        ls = loss_scale if loss_scale else 1.0 / (3 * H * W)
+        for i in range(n):
+            want_loss, want_g = fo.loss_grad(widths, params[i].astype(np.float64), targets[i], None)
+            want_loss, want_g = want_loss * ls * 3 * H * W, want_g * ls * 3 * H * W
+            assert abs(loss[i] - want_loss) <= 2e-5 * want_loss
+            assert np.abs(grad[i] - want_g).max() <= 2e-5 * np.abs(want_g).max(), (loss_scale, i)
+
+    for ls in (0.0, 1e-9, 1.0, 1e3):
+        check(tgt, tgt_d, p0, ls)
+    far = (tgt * 40.0 - 7.0).astype(np.float32)                       # errors of tens, not fractions
+    import torch
+    check(far, torch.from_numpy(far).cuda(), p0, 0.0)
+    f.steps(tgt_d, 60, 1e-3, t0=0, T=60)                              # the scale now follows the steps' own error
+    check(tgt, tgt_d, f.get_params(), 0.0)
+    check(far, torch.from_numpy(far).cuda(), f.get_params(), 0.0)        # ... and is wrong by two orders for these targets
     f.close()
 
 
