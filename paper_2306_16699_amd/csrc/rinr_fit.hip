@@ -1,5 +1,6 @@
-// Fitting one sine MLP per image on the GPU (Eq. 1): full-batch gradient of the squared error by
-// forward and backward passes on the fp32 matrix cores, Adam update fused into the same kernel.
+// Fitting one sine MLP per image on the GPU (Eq. 1): full-batch gradient of the squared error by forward and backward
+// passes on the matrix cores, Adam update fused into the same kernel.  This file: the handle, the fp32 kernels described
+// next, the host side of both families; the split-precision kernels (fp16 hi/lo operand pairs) are rinr_fit16.hip.h.
 //
 // One workgroup per image, one launch per step.  The image's weights live in LDS (bias folded in as an
 // extra input column that multiplies a row of ones), pixels are taken in chunks of PC, and every
@@ -112,6 +113,7 @@ struct FitArgs {
     uint32_t HW, W;
     float inv2W, inv2H, lo, span, w0rev;        // w0rev = w0 / 2pi
     float loss_scale;
+    float neg1;                   // -1, as data: keeps x - float(half) a single mixed-precision fma in the split kernels
     float lr, c1inv, c2inv, b1, b2, eps;
     int32_t L;
     int32_t d[kMaxL + 1];         // true widths
@@ -420,26 +422,27 @@ int lds_floats(int wq, int L) {
 // ---- the split-precision kernels (rinr_fit16.hip.h): built per hidden width rounded up to a multiple of 16 and per depth bucket
 constexpr int fit16_depth_lo(int wp) { return wp == 16 ? 4 : 6; }
 constexpr int fit16_depth_hi(int wp) { return wp <= 32 ? kMaxL : (wp == 48 ? 10 : 6); }
-template <int WP> fit_fn kernel16_of(int L) {
-    if (L <= fit16_depth_lo(WP)) return fit16::fit16_step_kernel<WP, fit16_depth_lo(WP)>;
-    return fit16::fit16_step_kernel<WP, fit16_depth_hi(WP)>;
+// Plane sets: two layers per pair of barriers where LDS holds two sets of pixel planes (padded widths 16 and 32), else one.
+template <int WP, int PL> fit_fn kernel16_of(int L) {
+    if (L <= fit16_depth_lo(WP)) return fit16::fit16_step_kernel<WP, fit16_depth_lo(WP), PL>;
+    return fit16::fit16_step_kernel<WP, fit16_depth_hi(WP), PL>;
 }
-fit_fn kernel16_for(int wp, int L) {
+fit_fn kernel16_for(int wp, int L, int pl) {
     switch (wp) {
-        case 16: return kernel16_of<16>(L);
-        case 32: return kernel16_of<32>(L);
-        case 48: return kernel16_of<48>(L);
-        default: return kernel16_of<64>(L);
+        case 16: return pl == 2 ? kernel16_of<16, 2>(L) : kernel16_of<16, 1>(L);
+        case 32: return pl == 2 ? kernel16_of<32, 2>(L) : kernel16_of<32, 1>(L);
+        case 48: return kernel16_of<48, 1>(L);
+        default: return kernel16_of<64, 1>(L);
     }
 }
-// LDS bytes of a model of L linear layers at padded width wp, or 0 if no split kernel is built that deep
-uint32_t lds_bytes16(int wp, int L) {
-    if (L > fit16_depth_hi(wp)) return 0;
+// LDS bytes of a model of L linear layers at padded width wp with pl plane sets, or 0 if no split kernel is built that deep
+uint32_t lds_bytes16(int wp, int L, int pl) {
+    if (L > fit16_depth_hi(wp) || (pl == 2 && wp > 32)) return 0;
     switch (wp) {
-        case 16: return fit16::Shape<16>::total(L);
-        case 32: return fit16::Shape<32>::total(L);
-        case 48: return fit16::Shape<48>::total(L);
-        default: return fit16::Shape<64>::total(L);
+        case 16: return pl == 2 ? fit16::Shape<16, 2>::total(L) : fit16::Shape<16, 1>::total(L);
+        case 32: return pl == 2 ? fit16::Shape<32, 2>::total(L) : fit16::Shape<32, 1>::total(L);
+        case 48: return fit16::Shape<48, 1>::total(L);
+        default: return fit16::Shape<64, 1>::total(L);
     }
 }
 
@@ -453,6 +456,7 @@ struct rinr_fit {
     int family;                 // RINR_FIT_KERNEL_FP32 or RINR_FIT_KERNEL_SPLIT16: the kernels this handle's steps run
     int wp;                     // widest hidden layer rounded up to a multiple of 16 (split kernels)
     uint32_t lds16;             // their LDS bytes
+    int pl16;                   // their plane sets (layers per pair of barriers)
     float *emag;                // [n_images] error size seen by the last step (split kernels' error scale); 0 = none yet
     int32_t p_off[kMaxL];
     float *params, *m, *v, *loss, *scratch_grad;
@@ -485,8 +489,13 @@ extern "C" int rinr_fit_create_ex(const rinr_fit_arch *arch, int64_t n_images, i
     f->wp = (wmax + 15) / 16 * 16;
     f->lds_floats = lds_floats(f->wq, arch->n_layers);
     if ((size_t)f->lds_floats * 4 + 256 > kLdsLimit) f->lds_floats = 0;
-    f->lds16 = lds_bytes16(f->wp, arch->n_layers);
-    if ((size_t)f->lds16 + 256 > kLdsLimit) f->lds16 = 0;
+    f->pl16 = 2;
+    f->lds16 = lds_bytes16(f->wp, arch->n_layers, 2);
+    if (f->lds16 == 0 || (size_t)f->lds16 + 256 > kLdsLimit) {
+        f->pl16 = 1;
+        f->lds16 = lds_bytes16(f->wp, arch->n_layers, 1);
+        if ((size_t)f->lds16 + 256 > kLdsLimit) f->lds16 = 0;
+    }
     // the split-precision kernels where they are built for the shape, the fp32 ones otherwise or on request
     f->family = (f->lds16 && !(flags & RINR_FIT_FLAG_FP32_MFMA)) ? RINR_FIT_KERNEL_SPLIT16 : RINR_FIT_KERNEL_FP32;
     if (f->family == RINR_FIT_KERNEL_FP32 && f->lds_floats == 0) { delete f; return RINR_E_UNSUPPORTED; }
@@ -501,7 +510,7 @@ extern "C" int rinr_fit_create_ex(const rinr_fit_arch *arch, int64_t n_images, i
     f->keep = nullptr;
     f->has_keep = false;
     f->t = 0;
-    const void *fn = f->family == RINR_FIT_KERNEL_SPLIT16 ? (const void *)kernel16_for(f->wp, arch->n_layers)
+    const void *fn = f->family == RINR_FIT_KERNEL_SPLIT16 ? (const void *)kernel16_for(f->wp, arch->n_layers, f->pl16)
                                                          : (const void *)kernel_for(f->wq, arch->n_layers);
     if (hip_fail(hipMalloc((void **)&f->params, np * 4)) || hip_fail(hipMalloc((void **)&f->m, np * 4)) ||
         hip_fail(hipMalloc((void **)&f->v, np * 4)) || hip_fail(hipMalloc((void **)&f->keep, np)) ||
@@ -619,6 +628,7 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     a.span = f->arch.coord_hi - f->arch.coord_lo;
     a.w0rev = (float)((double)f->arch.w0 / (2.0 * 3.14159265358979323846));
     a.loss_scale = loss_scale;
+    a.neg1 = -1.0f;
     {
         const int L = f->arch.n_layers;
         double c = 1.0;                                   // 1 / c_l
@@ -635,7 +645,7 @@ int launch(rinr_fit *f, const float *targets, float loss_scale, float lr, int64_
     for (int l = 0; l <= a.L; ++l) a.d[l] = f->arch.widths[l];
     for (int l = 0; l < a.L; ++l) a.p_off[l] = f->p_off[l];
     if (f->family == RINR_FIT_KERNEL_SPLIT16)
-        hipLaunchKernelGGL(kernel16_for(f->wp, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit16::fit16_waves(f->wp)), (size_t)f->lds16, stream, a);
+        hipLaunchKernelGGL(kernel16_for(f->wp, f->arch.n_layers, f->pl16), dim3((uint32_t)f->n_images), dim3(64 * fit16::fit16_waves(f->wp)), (size_t)f->lds16, stream, a);
     else
         hipLaunchKernelGGL(kernel_for(f->wq, f->arch.n_layers), dim3((uint32_t)f->n_images), dim3(64 * fit_waves(f->wq)), (size_t)f->lds_floats * 4, stream, a);
     FIT_HIP(hipGetLastError());

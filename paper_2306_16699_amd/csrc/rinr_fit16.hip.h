@@ -39,7 +39,7 @@ typedef float f2v __attribute__((ext_vector_type(2)));
 constexpr int fit16_waves(int wp) { return wp == 16 ? 4 : 8; }
 
 // Shapes and the LDS layout (bytes) for hidden widths <= WP (a multiple of 16) and L linear layers.
-template <int WP> struct Shape {
+template <int WP, int PL = 1> struct Shape {
     static constexpr int NW = fit16_waves(WP), NTHREADS = 64 * NW, PC = 16 * NW, KS = PC / 32;   // wavefronts, threads, pixels per chunk, 32-pixel steps
     static constexpr int MT = WP / 16;            // 16-row tiles of a hidden layer
     static constexpr int NIT = MT + 1;            // column tiles of a weight gradient: the inputs, then the tile whose first column is the bias
@@ -55,7 +55,8 @@ template <int WP> struct Shape {
     static __host__ __device__ constexpr uint32_t off_el(int L) { return off_eh(L) + 2u * PC * EP; }
     static __host__ __device__ constexpr uint32_t off_hh(int L) { return off_el(L) + 2u * PC * EP; }
     static __host__ __device__ constexpr uint32_t off_hl(int L) { return off_hh(L) + 2u * PC * HP; }
-    static __host__ __device__ constexpr uint32_t off_misc(int L) { return off_hl(L) + 2u * PC * HP; }   // float [16 + 16 + 16 * 8]: factors, scales, partial sums
+    static constexpr uint32_t SET = 4u * PC * (EP + HP);                                                // bytes of one set of planes (error hi, lo; input hi, lo)
+    static __host__ __device__ constexpr uint32_t off_misc(int L) { return off_eh(L) + PL * SET; }   // float [16 + 16 + 16 * 8]: factors, scales, partial sums
     static __host__ __device__ constexpr uint32_t total(int L) { return off_misc(L) + 4u * (32 + 16 * 8); }
 };
 
@@ -76,20 +77,22 @@ __device__ __forceinline__ h4v read_tr(const char *p) {
     const s4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v *)p);
     return __builtin_bit_cast(h4v, v);
 }
-// exact hi/lo split of a quad, round to nearest (activations, |x| <= 1)
-__device__ __forceinline__ void split_rne(f32x4 x, h4v &hi, h4v &lo) {
+// exact hi/lo split of a quad, round to nearest (activations, |x| <= 1).  neg1 is -1.0f passed as data, so that
+// x - float(hi) stays one mixed-precision fma instead of a conversion and a subtraction.
+__device__ __forceinline__ void split_rne(f32x4 x, float neg1, h4v &hi, h4v &lo) {
     const f2v p0 = {x[0], x[1]}, p1 = {x[2], x[3]};
     const h2v a0 = __builtin_convertvector(p0, h2v), a1 = __builtin_convertvector(p1, h2v);
-    const f2v r0 = {x[0] - (float)a0[0], x[1] - (float)a0[1]}, r1 = {x[2] - (float)a1[0], x[3] - (float)a1[1]};
+    const f2v r0 = {__builtin_fmaf((float)a0[0], neg1, x[0]), __builtin_fmaf((float)a0[1], neg1, x[1])};
+    const f2v r1 = {__builtin_fmaf((float)a1[0], neg1, x[2]), __builtin_fmaf((float)a1[1], neg1, x[3])};
     const h2v b0 = __builtin_convertvector(r0, h2v), b1 = __builtin_convertvector(r1, h2v);
     hi = (h4v){a0[0], a0[1], a1[0], a1[1]};
     lo = (h4v){b0[0], b0[1], b1[0], b1[1]};
 }
 // hi/lo split of a quad, round toward zero: values beyond the largest half saturate there instead of becoming infinite
-__device__ __forceinline__ void split_rtz(f32x4 x, h4v &hi, h4v &lo) {
+__device__ __forceinline__ void split_rtz(f32x4 x, float neg1, h4v &hi, h4v &lo) {
     const auto a0 = __builtin_amdgcn_cvt_pkrtz(x[0], x[1]), a1 = __builtin_amdgcn_cvt_pkrtz(x[2], x[3]);
-    const auto b0 = __builtin_amdgcn_cvt_pkrtz(x[0] - (float)a0[0], x[1] - (float)a0[1]);
-    const auto b1 = __builtin_amdgcn_cvt_pkrtz(x[2] - (float)a1[0], x[3] - (float)a1[1]);
+    const auto b0 = __builtin_amdgcn_cvt_pkrtz(__builtin_fmaf((float)a0[0], neg1, x[0]), __builtin_fmaf((float)a0[1], neg1, x[1]));
+    const auto b1 = __builtin_amdgcn_cvt_pkrtz(__builtin_fmaf((float)a1[0], neg1, x[2]), __builtin_fmaf((float)a1[1], neg1, x[3]));
     hi = (h4v){(_Float16)a0[0], (_Float16)a0[1], (_Float16)a1[0], (_Float16)a1[1]};
     lo = (h4v){(_Float16)b0[0], (_Float16)b0[1], (_Float16)b1[0], (_Float16)b1[1]};
 }
@@ -107,9 +110,9 @@ template <int WP> __device__ __forceinline__ int param_index(const FitArgs &a, i
     return j < din ? a.p_off[l] + o * din + j : -1;
 }
 
-template <int WP, int ML>
+template <int WP, int ML, int PL>
 __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4) ? 4 : 2) void fit16_step_kernel(const FitArgs a) {
-    typedef Shape<WP> S;
+    typedef Shape<WP, PL> S;
     constexpr int kWaves = S::NW, kThreads = S::NTHREADS, kPC = S::PC;
     constexpr int MT = S::MT, NP = (MT + 1) / 2, WPP = S::WPP, EP = S::EP, HP = S::HP, GSLOTS = S::GSLOTS;
     const h4v zh = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
@@ -121,9 +124,10 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
     const size_t img = blockIdx.x;
     float *P = a.params + img * a.n_params;
     const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float neg1 = a.neg1;
     const int L0 = a.L;
     float *const misc = (float *)(lds + S::off_misc(L0));      // [0..15] gradient factor per layer, [16..31] scale r per layer, [32..] partial sums
-    char *const EH = lds + S::off_eh(L0), *const EL = lds + S::off_el(L0), *const HH = lds + S::off_hh(L0), *const HL = lds + S::off_hl(L0);
+    char *const EH0 = lds + S::off_eh(L0), *const EL0 = lds + S::off_el(L0), *const HH0 = lds + S::off_hh(L0), *const HL0 = lds + S::off_hl(L0);   // set 0; set j is j * S::SET further
 
     // ---- set up: zero everything; weights as hi/lo planes (sine layers times w0 / 2pi: Z comes out in revolutions), biases,
     //      the unit of ones; per layer the sum of squared weights (for the error's scale), summed in a fixed order
@@ -155,7 +159,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
         for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
         if (lane == 0) misc[32 + l * 8 + wave] = ss;
     }
-    for (int p = tid; p < kPC; p += kThreads) ((_Float16 *)HH)[p * HP + WP] = (_Float16)1.0f;
+    for (int p = tid; p < kPC * PL; p += kThreads) ((_Float16 *)(HH0 + (p / kPC) * S::SET))[(p % kPC) * HP + WP] = (_Float16)1.0f;
     __syncthreads();
     if (tid == 0) {
         // scale of the output layer's error from the error the previous step saw; then down the layers by the estimated gains
@@ -216,7 +220,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
                     z[v] = fmaf(w.x, x, fmaf(w.y, y, w.z));
                 }
                 zst[0][t] = z;
-                split_rne(sin4(z), Bh[t], Bl[t]);
+                split_rne(sin4(z), neg1, Bh[t], Bl[t]);
             }
         }
 #pragma unroll
@@ -230,14 +234,14 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
 #pragma unroll
                     for (int j = 0; j < NP; ++j) {
                         const int at = 2 * ((16 * mt + n) * WPP + 32 * j + 4 * g);
-                        const bool two = 2 * j + 1 < MT;
-                        const h8v ah = cat(*(const h4v *)(Wh + at), two ? *(const h4v *)(Wh + at + 32) : zh), al = cat(*(const h4v *)(Wl + at), two ? *(const h4v *)(Wl + at + 32) : zh);
+                        const bool two = 2 * j + 1 < MT;      // an odd last tile: the B operand's other half is zero, the A operand's is whatever follows in LDS (finite halfs)
+                        const h8v ah = cat(*(const h4v *)(Wh + at), *(const h4v *)(Wh + at + 32)), al = cat(*(const h4v *)(Wl + at), *(const h4v *)(Wl + at + 32));
                         z = mfma3(ah, al, cat(Bh[2 * j], two ? Bh[2 * j + 1] : zh), cat(Bl[2 * j], two ? Bl[2 * j + 1] : zh), z);
                     }
                     zst[l][mt] = z;
                 }
 #pragma unroll
-                for (int t = 0; t < MT; ++t) split_rne(sin4(zst[l][t]), Bh[t], Bl[t]);
+                for (int t = 0; t < MT; ++t) split_rne(sin4(zst[l][t]), neg1, Bh[t], Bl[t]);
             }
         }
         f32x4 E[MT];                       // the error at hand, scaled (see the file header); the output layer's is tile 0
@@ -250,7 +254,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
             for (int j = 0; j < NP; ++j) {
                 const int at = 2 * (n * WPP + 32 * j + 4 * g);
                 const bool two = 2 * j + 1 < MT;
-                const h8v ah = cat(*(const h4v *)(Wh + at), two ? *(const h4v *)(Wh + at + 32) : zh), al = cat(*(const h4v *)(Wl + at), two ? *(const h4v *)(Wl + at + 32) : zh);
+                const h8v ah = cat(*(const h4v *)(Wh + at), *(const h4v *)(Wh + at + 32)), al = cat(*(const h4v *)(Wl + at), *(const h4v *)(Wl + at + 32));
                 z = mfma3(ah, al, cat(Bh[2 * j], two ? Bh[2 * j + 1] : zh), cat(Bl[2 * j], two ? Bl[2 * j + 1] : zh), z);
             }
             const float eo = misc[16 + L - 1];
@@ -263,92 +267,118 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
             }
         }
 
-        // ---- backward, layer by layer: the error and the layer's input go to LDS as hi/lo planes for the weight gradient,
-        //      the error goes down one layer in registers, then (after a barrier) the owned gradient tiles take the chunk
+        // ---- backward, PL layers at a time: each wavefront writes its pixels' error and layer input of those layers to LDS
+        //      as hi/lo planes (one set per layer) and takes the error down through them in registers; after a barrier the
+        //      weight-gradient tiles of those layers take the chunk's pixels, spread round-robin over the wavefronts
 #pragma unroll
-        for (int l = ML - 1; l >= 0; --l) {
-            if (l < L) {
-                const bool last = l == L - 1;
-                h4v Eh[MT], El[MT];
+        for (int lg = ML - 1; lg >= 0; lg -= PL) {
+            const int llow = lg - PL + 1 > 0 ? lg - PL + 1 : 0;
+            if (llow < L) {
 #pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    if (t == 0 || !last) {
-                        split_rtz(E[t], Eh[t], El[t]);
-                        const int at = 2 * (pc * EP + 16 * t + 4 * g);
-                        *(h4v *)(EH + at) = Eh[t];
-                        *(h4v *)(EL + at) = El[t];
-                    }
-                }
-                const int uo = ones_unit<WP>(a.d[l]);          // < WP: the unit of ones sits inside a tile and is written with it
-                if (l == 0) {
-                    if (g == 0) {
-                        h4v hi, lo;
-                        split_rne((f32x4){x, y, 1.0f, 0.0f}, hi, lo);
-                        *(h4v *)(HH + 2 * (pc * HP)) = hi;
-                        *(h4v *)(HL + 2 * (pc * HP)) = lo;
-                    }
-                } else {
+                for (int j = 0; j < PL; ++j) {
+                    const int l = lg - j;
+                    if (l >= 0 && l < L) {
+                        const bool last = l == L - 1;
+                        char *const EH = EH0 + j * S::SET, *const EL = EL0 + j * S::SET, *const HH = HH0 + j * S::SET, *const HL = HL0 + j * S::SET;
+                        h4v Eh[MT], El[MT];
 #pragma unroll
-                    for (int t = 0; t < MT; ++t) {
-                        h4v hi, lo;
-                        split_rne(sin4(zst[l - 1][t]), hi, lo);
-                        if (16 * t + 4 * g == (uo & ~3)) {           // the padded unit there is 0: make it 1
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) hi[v] = v == (uo & 3) ? (_Float16)1.0f : hi[v];
-                        }
-                        const int at = 2 * (pc * HP + 16 * t + 4 * g);
-                        *(h4v *)(HH + at) = hi;
-                        *(h4v *)(HL + at) = lo;
-                    }
-                    // E_{l-1} = (W_l^T E_l) cos(2 pi z_{l-1}) r: the transposed operand straight from the row-major planes
-                    const char *Wh = lds + (last ? S::off_last(L) : S::off_hid(l, L)), *Wl = Wh + 2 * (last ? 16 : WP) * WPP;
-                    const float r = misc[16 + l - 1];
-                    const int e4 = n >> 2, q4 = n & 3;
-#pragma unroll
-                    for (int it = 0; it < MT; ++it) {
-                        f32x4 gacc = zero4;
-#pragma unroll
-                        for (int j = 0; j < NP; ++j) {
-                            if (j == 0 || !last) {
-                                const int at = 2 * ((32 * j + 4 * g + e4) * WPP + 16 * it + 4 * q4);
-                                const bool two = 2 * j + 1 < MT && !last;
-                                const h8v ah = cat(read_tr(Wh + at), two ? read_tr(Wh + at + 32 * WPP) : zh), al = cat(read_tr(Wl + at), two ? read_tr(Wl + at + 32 * WPP) : zh);
-                                gacc = mfma3(ah, al, cat(Eh[2 * j], two ? Eh[2 * j + 1] : zh), cat(El[2 * j], two ? El[2 * j + 1] : zh), gacc);
+                        for (int t = 0; t < MT; ++t) {
+                            split_rtz(E[t], neg1, Eh[t], El[t]);            // (the output layer's error has one tile; the others are zero)
+                            if (t == 0 || !last) {
+                                const int at = 2 * (pc * EP + 16 * t + 4 * g);
+                                *(h4v *)(EH + at) = Eh[t];
+                                *(h4v *)(EL + at) = El[t];
                             }
                         }
-                        const f32x4 z = zst[l - 1][it];
+                        const int uo = ones_unit<WP>(a.d[l]);          // < WP: the unit of ones sits inside a tile and is written with it
+                        if (l == 0) {
+                            if (g == 0) {
+                                h4v hi, lo;
+                                split_rne((f32x4){x, y, 1.0f, 0.0f}, neg1, hi, lo);
+                                *(h4v *)(HH + 2 * (pc * HP)) = hi;
+                                *(h4v *)(HL + 2 * (pc * HP)) = lo;
+                            }
+                        } else {
+                            // E_{l-1} = (W_l^T E_l) cos(2 pi z_{l-1}) r: the transposed operand straight from the row-major planes
+                            const char *Wh = lds + (last ? S::off_last(L) : S::off_hid(l, L)), *Wl = Wh + 2 * (last ? 16 : WP) * WPP;
+                            const float r = misc[16 + l - 1];
+                            const int e4 = n >> 2, q4 = n & 3;
+                            f32x4 gacc[MT];
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) E[it][v] = gacc[v] * (__builtin_amdgcn_cosf(z[v]) * r);
+                            for (int it = 0; it < MT; ++it) {
+                                gacc[it] = zero4;
+#pragma unroll
+                                for (int jp = 0; jp < NP; ++jp) {
+                                    if (jp == 0 || !last) {
+                                        const int at = 2 * ((32 * jp + 4 * g + e4) * WPP + 16 * it + 4 * q4);
+                                        const bool two = 2 * jp + 1 < MT;     // rows past the layer's own: whatever follows in LDS, times an error of zero
+                                        const h8v ah = cat(read_tr(Wh + at), read_tr(Wh + at + 32 * WPP)), al = cat(read_tr(Wl + at), read_tr(Wl + at + 32 * WPP));
+                                        gacc[it] = mfma3(ah, al, cat(Eh[2 * jp], two ? Eh[2 * jp + 1] : zh), cat(El[2 * jp], two ? El[2 * jp + 1] : zh), gacc[it]);
+                                    }
+                                }
+                            }
+                            // the layer's input again (sine of the kept pre-activations) for the weight gradient, while the matrix steps run
+#pragma unroll
+                            for (int t = 0; t < MT; ++t) {
+                                h4v hi, lo;
+                                split_rne(sin4(zst[l - 1][t]), neg1, hi, lo);
+                                const int at = 2 * (pc * HP + 16 * t + 4 * g);
+                                *(h4v *)(HH + at) = hi;
+                                *(h4v *)(HL + at) = lo;
+                            }
+                            // the unit of ones inside a tile: the padded unit there was written as 0 by the lane that owns it; that lane
+                            // makes it 1 (same lane, later store: program order)
+                            if (uo < WP && 4 * g == (uo & 12)) ((_Float16 *)HH)[pc * HP + uo] = (_Float16)1.0f;
+#pragma unroll
+                            for (int it = 0; it < MT; ++it) {
+                                const f32x4 z = zst[l - 1][it];
+                                const f32x4 c = {__builtin_amdgcn_cosf(z[0]), __builtin_amdgcn_cosf(z[1]), __builtin_amdgcn_cosf(z[2]), __builtin_amdgcn_cosf(z[3])};
+                                E[it] = gacc[it] * (c * r);
+                            }
+                        }
                     }
                 }
                 __syncthreads();
-                // dW_l += E_l H_l^T over the chunk's pixels: tile (rows ot, columns it), 16 pixels per matrix step
-                {
-                    int nit = uo / 16 + 1;                           // column tiles up to the one with the unit of ones
-                    asm volatile("" : "+s"(nit));                  // a scalar, derived again per chunk: not a set of per-layer values held across the loop
-                    const int ntasks = (last ? 1 : MT) * nit;
-                    const int e4 = n >> 2, q4 = n & 3;
+                int rot = 0;
 #pragma unroll
-                    for (int s = 0; s < GSLOTS; ++s) {
-                        const int task = wave + s * kWaves;
-                        if (task < ntasks) {
-                            int ot = 0;
+                for (int j = 0; j < PL; ++j) {
+                    const int l = lg - j;
+                    if (l >= 0 && l < L) {
+                        // dW_l += E_l H_l^T over the chunk's pixels: tile (rows ot, columns it), 32 pixels per matrix step
+                        {
+                            const bool last = l == L - 1;
+                            const int uo = ones_unit<WP>(a.d[l]);
+                            const char *const EH = EH0 + j * S::SET, *const EL = EL0 + j * S::SET, *const HH = HH0 + j * S::SET, *const HL = HL0 + j * S::SET;
+                            int nit = uo / 16 + 1;                           // column tiles up to the one with the unit of ones
+                            asm volatile("" : "+s"(nit));                  // a scalar, derived again per chunk: not a set of per-layer values held across the loop
+                            const int ntasks = (last ? 1 : MT) * nit;
+                            const int e4 = n >> 2, q4 = n & 3;
+                            // the group's layers start their round-robin over the wavefronts where the layer before stopped
+                            const int wv = (wave + kWaves - rot % kWaves) % kWaves;
+                            rot += ntasks;
 #pragma unroll
-                            for (int q = 1; q < MT; ++q) ot += task >= q * nit ? 1 : 0;
-                            const int it = task - ot * nit;
-                            f32x4 d0 = zero4, d1 = zero4, d2 = zero4;        // one chain per term: the matrix steps of a tile do not wait for each other
+                            for (int s = 0; s < GSLOTS; ++s) {
+                                const int task = wv + s * kWaves;
+                                if (task < ntasks) {
+                                    int ot = 0;
 #pragma unroll
-                            for (int k = 0; k < kPC / 32; ++k) {
-                                const int px = 32 * k + 4 * g + e4;
-                                const int ea = 2 * (px * EP + 16 * ot + 4 * q4), ha = 2 * (px * HP + 16 * it + 4 * q4);
-                                const h8v eh = cat(read_tr(EH + ea), read_tr(EH + ea + 32 * EP)), el = cat(read_tr(EL + ea), read_tr(EL + ea + 32 * EP));
-                                const h8v hh = cat(read_tr(HH + ha), read_tr(HH + ha + 32 * HP)), hl = cat(read_tr(HL + ha), read_tr(HL + ha + 32 * HP));
-                                d0 = mfma32(eh, hh, d0);
-                                d1 = mfma32(eh, hl, d1);
-                                d2 = mfma32(el, hh, d2);
+                                    for (int q = 1; q < MT; ++q) ot += task >= q * nit ? 1 : 0;
+                                    const int it = task - ot * nit;
+                                    f32x4 d0 = zero4, d1 = zero4, d2 = zero4;        // one chain per term: the matrix steps of a tile do not wait for each other
+#pragma unroll
+                                    for (int k = 0; k < kPC / 32; ++k) {
+                                        const int px = 32 * k + 4 * g + e4;
+                                        const int ea = 2 * (px * EP + 16 * ot + 4 * q4), ha = 2 * (px * HP + 16 * it + 4 * q4);
+                                        const h8v eh = cat(read_tr(EH + ea), read_tr(EH + ea + 32 * EP)), el = cat(read_tr(EL + ea), read_tr(EL + ea + 32 * EP));
+                                        const h8v hh = cat(read_tr(HH + ha), read_tr(HH + ha + 32 * HP)), hl = cat(read_tr(HL + ha), read_tr(HL + ha + 32 * HP));
+                                        d0 = mfma32(eh, hh, d0);
+                                        d1 = mfma32(eh, hl, d1);
+                                        d2 = mfma32(el, hh, d2);
+                                    }
+                                    const f32x4 d = acc[l][s] + (d0 + (d1 + d2));
+                                    acc[l][s] = d;
+                                }
                             }
-                            const f32x4 d = acc[l][s] + (d0 + (d1 + d2));
-                            acc[l][s] = d;
                         }
                     }
                 }
@@ -375,34 +405,41 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
     const uint8_t *K = a.keep ? a.keep + img * a.n_params : nullptr;
     float *G = a.grad_out ? a.grad_out + img * a.n_params : nullptr;
 #pragma unroll
-    for (int l = 0; l < ML; ++l) {
-        if (l < L) {
-            const int nit = ones_unit<WP>(a.d[l]) / 16 + 1, ntasks = (l == L - 1 ? 1 : MT) * nit;
-            const float gs = misc[l];
+    for (int lg = ML - 1; lg >= 0; lg -= PL) {
+        int rot = 0;
 #pragma unroll
-            for (int s = 0; s < GSLOTS; ++s) {
-                const int task = wave + s * kWaves;
-                if (task < ntasks) {
-                    int ot = 0;
+        for (int j = 0; j < PL; ++j) {
+            const int l = lg - j;
+            if (l >= 0 && l < L) {
+                const int nit = ones_unit<WP>(a.d[l]) / 16 + 1, ntasks = (l == L - 1 ? 1 : MT) * nit;
+                const int wv = (wave + kWaves - rot % kWaves) % kWaves;        // the same owner as in the loop above
+                rot += ntasks;
+                const float gs = misc[l];
 #pragma unroll
-                    for (int q = 1; q < MT; ++q) ot += task >= q * nit ? 1 : 0;
-                    const int it = task - ot * nit;
+                for (int s = 0; s < GSLOTS; ++s) {
+                    const int task = wv + s * kWaves;
+                    if (task < ntasks) {
+                        int ot = 0;
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int at = param_index<WP>(a, l, ot * 16 + 4 * g + v, it * 16 + n);
-                        if (at >= 0) {
-                            const bool kept = !K || K[at];
-                            const float gr = kept ? acc[l][s][v] * gs : 0.0f;
-                            if (G) {
-                                G[at] = gr;
-                            } else if (kept) {
-                                const float mm = a.b1 * M[at] + (1.0f - a.b1) * gr;
-                                const float vv = a.b2 * V[at] + (1.0f - a.b2) * gr * gr;
-                                M[at] = mm;
-                                V[at] = vv;
-                                P[at] -= a.lr * (mm * a.c1inv) / (sqrtf(vv * a.c2inv) + a.eps);
-                            } else {
-                                P[at] = 0.0f;
+                        for (int q = 1; q < MT; ++q) ot += task >= q * nit ? 1 : 0;
+                        const int it = task - ot * nit;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int at = param_index<WP>(a, l, ot * 16 + 4 * g + v, it * 16 + n);
+                            if (at >= 0) {
+                                const bool kept = !K || K[at];
+                                const float gr = kept ? acc[l][s][v] * gs : 0.0f;
+                                if (G) {
+                                    G[at] = gr;
+                                } else if (kept) {
+                                    const float mm = a.b1 * M[at] + (1.0f - a.b1) * gr;
+                                    const float vv = a.b2 * V[at] + (1.0f - a.b2) * gr * gr;
+                                    M[at] = mm;
+                                    V[at] = vv;
+                                    P[at] -= a.lr * (mm * a.c1inv) / (sqrtf(vv * a.c2inv) + a.eps);
+                                } else {
+                                    P[at] = 0.0f;
+                                }
                             }
                         }
                     }

@@ -18,6 +18,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "paper_2306_16699_amd", "csrc", "rinr_api.hip")
+FIT_SRC = os.path.join(ROOT, "paper_2306_16699_amd", "csrc", "rinr_fit.hip")
 MIN_WAIT_STATES = 20
 
 MFMA = re.compile(r"^\s+(v_mfma_\w+)\s+([av])\[(\d+):(\d+)\],\s*\S+,\s*\S+,\s*(?:([av])\[(\d+):(\d+)\]|\S+)")
@@ -109,3 +110,22 @@ def test_mixed_depth_matrix_steps_stay_apart(tmp_path):
             bad.append((name, worst))
     assert n_kernels >= 20 and n_pairs >= 10, (n_kernels, n_pairs)   # the scan found the kernels and the mixed-depth pairs
     assert not bad, bad
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not found")
+def test_fit_kernels_use_one_matrix_opcode_per_accumulator(tmp_path):
+    """The fit kernels avoid the case altogether: each family uses a single matrix instruction (the split-precision ones
+    pad an odd last tile with zeros rather than take a half-depth step)."""
+    out = tmp_path / "rinr_fit.s"
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", "--cuda-device-only", "-S", "-o", str(out), FIT_SRC]
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.PIPE)
+    seen = 0
+    for name, body in kernels_of(out.read_text()):
+        if "step_kernel" not in name:
+            continue
+        ops = {m.group(1) for m in map(MFMA.match, body) if m}
+        assert len(ops) == 1, (name, ops)
+        assert scan_kernel(body) is None
+        seen += 1
+    assert seen >= 10, seen
