@@ -47,16 +47,21 @@ template <int WP, int PL = 1> struct Shape {
     static constexpr int EP = WP + 4;             // halfs per pixel of the error planes
     static constexpr int HP = WP + 20;            // halfs per pixel of the input planes: WP units, the unit of ones, 15 zero units, pad
     static constexpr int GSLOTS = (MT * NIT + NW - 1) / NW;   // gradient tiles a wavefront owns per layer
-    static __host__ __device__ constexpr uint32_t off_w0() { return 0; }                                  // float [WP][4]: x weight, y weight, bias, 0
-    static __host__ __device__ constexpr uint32_t off_bias(int l) { return WP * 16 + (uint32_t)l * WP * 4; }   // float [WP] per layer
-    static __host__ __device__ constexpr uint32_t off_hid(int l, int L) { return WP * 16 + (uint32_t)L * WP * 4 + (uint32_t)(l - 1) * 4u * WP * WPP; }   // hi plane, then lo plane
-    static __host__ __device__ constexpr uint32_t off_last(int L) { return off_hid(L - 1, L); }           // [16][WPP] hi, then lo
-    static __host__ __device__ constexpr uint32_t off_eh(int L) { return off_last(L) + 4u * 16 * WPP; }
-    static __host__ __device__ constexpr uint32_t off_el(int L) { return off_eh(L) + 2u * PC * EP; }
-    static __host__ __device__ constexpr uint32_t off_hh(int L) { return off_el(L) + 2u * PC * EP; }
-    static __host__ __device__ constexpr uint32_t off_hl(int L) { return off_hh(L) + 2u * PC * HP; }
+    // LDS, in this order: the sets of pixel planes, the first layer, the biases (12 slots), the hidden layers' weight planes,
+    // the output layer's, a pad, small tables.  Everything up to the hidden layers sits at compile-time offsets, so a lane's
+    // address is one register plus an immediate.  Reads that run past an operand's rows or columns (the other half of an
+    // odd last tile, whose partner operand is zero) land in what follows: weight planes, then the pad of zeros.
     static constexpr uint32_t SET = 4u * PC * (EP + HP);                                                // bytes of one set of planes (error hi, lo; input hi, lo)
-    static __host__ __device__ constexpr uint32_t off_misc(int L) { return off_eh(L) + PL * SET; }   // float [16 + 16 + 16 * 8]: factors, scales, partial sums
+    static __host__ __device__ constexpr uint32_t off_eh(int j) { return (uint32_t)j * SET; }
+    static __host__ __device__ constexpr uint32_t off_el(int j) { return off_eh(j) + 2u * PC * EP; }
+    static __host__ __device__ constexpr uint32_t off_hh(int j) { return off_el(j) + 2u * PC * EP; }
+    static __host__ __device__ constexpr uint32_t off_hl(int j) { return off_hh(j) + 2u * PC * HP; }
+    static __host__ __device__ constexpr uint32_t off_w0() { return PL * SET; }                           // float [WP][4]: x weight, y weight, bias, 0
+    static __host__ __device__ constexpr uint32_t off_bias(int l) { return off_w0() + WP * 16 + (uint32_t)l * WP * 4; }   // float [WP] per layer
+    static __host__ __device__ constexpr uint32_t off_hid(int l) { return off_bias(12) + (uint32_t)(l - 1) * 4u * WP * WPP; }   // hi plane, then lo plane
+    static __host__ __device__ constexpr uint32_t off_last(int L) { return off_hid(L - 1); }              // [16][WPP] hi, then lo
+    static constexpr uint32_t PAD = (2u * 16 * WPP + 15) / 16 * 16 + 64;
+    static __host__ __device__ constexpr uint32_t off_misc(int L) { return off_last(L) + 4u * 16 * WPP + PAD; }   // float [16 + 16 + 16 * 8]: factors, scales, partial sums
     static __host__ __device__ constexpr uint32_t total(int L) { return off_misc(L) + 4u * (32 + 16 * 8); }
 };
 
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
     const float neg1 = a.neg1;
     const int L0 = a.L;
     float *const misc = (float *)(lds + S::off_misc(L0));      // [0..15] gradient factor per layer, [16..31] scale r per layer, [32..] partial sums
-    char *const EH0 = lds + S::off_eh(L0), *const EL0 = lds + S::off_el(L0), *const HH0 = lds + S::off_hh(L0), *const HL0 = lds + S::off_hl(L0);   // set 0; set j is j * S::SET further
+    char *const EH0 = lds + S::off_eh(0), *const EL0 = lds + S::off_el(0), *const HH0 = lds + S::off_hh(0), *const HL0 = lds + S::off_hl(0);   // set 0; set j is j * S::SET further
 
     // ---- set up: zero everything; weights as hi/lo planes (sine layers times w0 / 2pi: Z comes out in revolutions), biases,
     //      the unit of ones; per layer the sum of squared weights (for the error's scale), summed in a fixed order
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
             for (int e = tid; e < dout * 2; e += kThreads) { const float w = src[e] * sc; W0[(e >> 1) * 4 + (e & 1)] = w; }
             for (int o = tid; o < dout; o += kThreads) W0[o * 4 + 2] = src[dout * din + o] * sc;
         } else {
-            _Float16 *Wh = (_Float16 *)(lds + (l == L0 - 1 ? S::off_last(L0) : S::off_hid(l, L0)));
+            _Float16 *Wh = (_Float16 *)(lds + (l == L0 - 1 ? S::off_last(L0) : S::off_hid(l)));
             _Float16 *Wl = Wh + (l == L0 - 1 ? 16 : WP) * WPP;
             float *B = (float *)(lds + S::off_bias(l));
             for (int e = tid; e < dout * din; e += kThreads) {
@@ -226,7 +231,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
 #pragma unroll
         for (int l = 1; l < ML - 1; ++l) {
             if (l < L - 1) {
-                const char *Wh = lds + S::off_hid(l, L), *Wl = Wh + 2 * WP * WPP;
+                const char *Wh = lds + S::off_hid(l), *Wl = Wh + 2 * WP * WPP;
                 const f32x4 *B = (const f32x4 *)(lds + S::off_bias(l));
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
@@ -300,7 +305,7 @@ __global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4
                             }
                         } else {
                             // E_{l-1} = (W_l^T E_l) cos(2 pi z_{l-1}) r: the transposed operand straight from the row-major planes
-                            const char *Wh = lds + (last ? S::off_last(L) : S::off_hid(l, L)), *Wl = Wh + 2 * (last ? 16 : WP) * WPP;
+                            const char *Wh = lds + (last ? S::off_last(L) : S::off_hid(l)), *Wl = Wh + 2 * (last ? 16 : WP) * WPP;
                             const float r = misc[16 + l - 1];
                             const int e4 = n >> 2, q4 = n & 3;
                             f32x4 gacc[MT];
