@@ -18,6 +18,10 @@ ARCHS = {
     "12 layers x 20": ([2] + [20] * 11 + [3], 10, 10),            # the deep kernel of the width-32 class, the API's depth limit
     "width 20": ([2, 20, 20, 3], 13, 11),                          # widths round up to 8: 24 ...
     "widths 50, 56": ([2, 50, 56, 50, 3], 10, 9),                 # ... and 56
+    "width 64 x3": ([2, 64, 64, 64, 3], 12, 11),                  # full padded widths: the bias unit takes a column tile of its own
+    "widths 48, 16 exact": ([2, 48, 16, 48, 3], 9, 14),
+    "widths 64, 17, 33": ([2, 64, 17, 33, 3], 8, 19),
+    "one unit between wide layers": ([2, 1, 64, 1, 3], 7, 6),
     "one hidden unit": ([2, 1, 3], 5, 7),
     "one pixel": ([2, 8, 3], 1, 1),
 }
