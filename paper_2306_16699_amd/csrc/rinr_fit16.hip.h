@@ -4,7 +4,7 @@
 // bits per product at a third of the fp32 matrix instruction's time, and the fp16 matrix pipe runs beside the vector ALU
 // that does the sines, cosines and splits.
 //
-// One workgroup per image, 8 wavefronts, pixels in chunks of 128: a wavefront owns 16 pixels of the chunk and takes them
+// One workgroup per image, 8 wavefronts (2 at padded width 16), pixels in chunks of 16 per wavefront: a wavefront owns 16 pixels of the chunk and takes them
 // through all layers forward and backward with the activations and errors in registers (lane = (pixel n, group g);
 // a 16-row tile of a layer's units is one quad of four registers per lane, rows 16 t + 4 g + v).  A quad is exactly
 // half of the B operand of one 32-deep matrix step (two tiles' quads side by side), so nothing moves between lanes from
@@ -34,9 +34,9 @@ typedef _Float16 h2v __attribute__((ext_vector_type(2)));
 typedef short s4v __attribute__((ext_vector_type(4)));
 typedef float f2v __attribute__((ext_vector_type(2)));
 
-// Wavefronts per workgroup: 8 (128 pixels per chunk); 4 at padded width 16, whose steps are so short that more, smaller
-// workgroups per CU hide the barriers better.
-constexpr int fit16_waves(int wp) { return wp == 16 ? 4 : 8; }
+// Wavefronts per workgroup: 8 (128 pixels per chunk); 2 at padded width 16 (32 pixels per chunk), whose phases are so short
+// that many small workgroups per CU, each at its own barrier, fill the machine better (3 x 15 at 32 x 32: 0.105 -> 0.092 ms).
+constexpr int fit16_waves(int wp) { return wp == 16 ? 2 : 8; }
 
 // Shapes and the LDS layout (bytes) for hidden widths <= WP (a multiple of 16) and L linear layers.
 template <int WP, int PL = 1> struct Shape {
@@ -116,7 +116,7 @@ template <int WP> __device__ __forceinline__ int param_index(const FitArgs &a, i
 }
 
 template <int WP, int ML, int PL>
-__global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW == 4 && ML <= 4) ? 4 : 2) void fit16_step_kernel(const FitArgs a) {
+__global__ __launch_bounds__(Shape<WP>::NTHREADS, (Shape<WP>::NW <= 4 && ML <= 4) ? 4 : 2) void fit16_step_kernel(const FitArgs a) {
     typedef Shape<WP, PL> S;
     constexpr int kWaves = S::NW, kThreads = S::NTHREADS, kPC = S::PC;
     constexpr int MT = S::MT, NP = (MT + 1) / 2, WPP = S::WPP, EP = S::EP, HP = S::HP, GSLOTS = S::GSLOTS;
