@@ -56,6 +56,29 @@ FIT_SHAPES = {
 }
 
 
+
+def time_fit_step(shape: str, fp32: bool, steps: int = 10, warm: int = 5):
+    """Mean duration of one Adam step (HIP events) of an encode-side shape, for the extra figures of the default line."""
+    import torch
+    from paper_2306_16699_amd import rinr_fit, synth
+    what, widths, n, H, W = FIT_SHAPES[shape]
+    base = torch.from_numpy(synth.images(1, 8, H, W)).cuda()
+    tgt = base.repeat((n + 7) // 8, 1, 1, 1)[:n].contiguous()
+    f = rinr_fit.Fit(widths, n, H, W, fp32=fp32)
+    f.set_params(np.tile(synth.init_params(2, widths, 8), ((n + 7) // 8, 1))[:n])
+    f.steps(tgt, warm, 5e-4)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    f.steps(tgt, steps, 5e-4, t0=0, T=steps)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / steps
+    fam = "split16" if f.kernel_family == rinr_fit.KERNEL_SPLIT16 else "fp32"
+    f.close()
+    return {"shape": what, "images": n, "kernels": fam, "ms_per_step": ms, "pixel_steps_per_s": n * H * W / (ms * 1e-3)}
+
+
 def bench_fit(args) -> int:
     """One step = one full-batch Adam step (every pixel) of every image's MLP.  The split-precision kernels are the default
     where they are built for the shape (--fp32-mfma takes the fp32 ones); the roofline is the matrix peak of the dtype the
@@ -123,6 +146,7 @@ def main() -> int:
                          "ramps up from idle over a few hundred ms; a handful of steps is timed on the ramp)")
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4, the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-encode-side", action="store_true", help="skip the short fit-step timings appended to the default line")
     ap.add_argument("--tile", type=int, default=0, help="experiment: MFMA tile rows for widths 32/64 (16 or 32)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--threads", type=int, default=0)
@@ -318,6 +342,10 @@ def main() -> int:
         res["fp16_act_mode"] = alt16
     if alt16a is not None:
         res["fp16_all_mode"] = alt16a
+    if args.config == 4 and not args.paper and not args.no_encode_side and not args.no_cpu_baseline:      # the full default run only
+        # the encode side (one Adam step of every image's fit, Eq. 1) on two of the paper's shapes, both kernel families:
+        # not part of `value`; `python bench.py --fit <shape>` is the full measurement
+        res["encode_side"] = [time_fit_step(sh, fp32) for sh in ("imagenet", "cifar") for fp32 in (False, True)]
 
     if not args.no_cpu_baseline:
         from oracle import oracle
