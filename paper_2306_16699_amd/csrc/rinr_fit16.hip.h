@@ -4,8 +4,8 @@
 // bits per product at a third of the fp32 matrix instruction's time, and the fp16 matrix pipe runs beside the vector ALU
 // that does the sines, cosines and splits.
 //
-// One workgroup per image, 8 wavefronts (2 at padded width 16), pixels in chunks of 16 per wavefront: a wavefront owns 16 pixels of the chunk and takes them
-// through all layers forward and backward with the activations and errors in registers (lane = (pixel n, group g);
+// One workgroup per image, 8 wavefronts (2 at padded width 16), 16 pixels of a chunk per wavefront: a wavefront takes its
+// pixels through all layers forward and backward with the activations and errors in registers (lane = (pixel n, group g);
 // a 16-row tile of a layer's units is one quad of four registers per lane, rows 16 t + 4 g + v).  A quad is exactly
 // half of the B operand of one 32-deep matrix step (two tiles' quads side by side), so nothing moves between lanes from
 // one layer to the next, in either direction.  The weights sit in LDS once, row-major [out][in] as a hi and a lo plane:
@@ -14,9 +14,10 @@
 // ds_read_b64_tr_b16 (within 16 lanes, lane i receives element i % 4 of the chunks that lanes i / 4, 4 + i / 4,
 // 8 + i / 4, 12 + i / 4 point at).  Only the weight gradient, which contracts over pixels, needs other wavefronts' data:
 // per layer every wavefront writes its pixels' error and layer input as hi/lo planes [pixel][unit] to LDS, and after a
-// barrier each wavefront accumulates the gradient tiles it owns over the chunk's 128 pixels, both operands read with the
-// transposing read.  Gradient tiles stay in their owner's registers for the whole step; Adam is applied in place at
-// the end, as in the fp32 kernel.
+// barrier each wavefront accumulates the gradient tiles it owns over the chunk's pixels, both operands read with the
+// transposing read; with PL sets of planes, PL layers share one pair of barriers.  The bias is the weight of a unit of
+// ones, placed right behind the layer's inputs where the padded width has room.  Gradient tiles stay in their owner's
+// registers for the whole step; Adam is applied in place at the end, as in the fp32 kernel.
 //
 // Range of the error in fp16: the error of layer l is carried times a power of two T_l.  T of the output layer is
 // chosen from the root-mean-square error the previous step saw (kept per image; 0.25 if there was none), so that the
