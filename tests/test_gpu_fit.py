@@ -149,6 +149,34 @@ def test_split_kernels_carry_the_error_at_any_size():
     f.close()
 
 
+@pytest.mark.parametrize("widths,H,W,steps,lr,tol", [([2, 15, 15, 3], 32, 32, 600, 2e-3, 2e-3),
+                                                     ([2] + [32] * 4 + [3], 40, 56, 400, 1e-3, 2e-2),
+                                                     ([2] + [40] * 9 + [3], 48, 48, 400, 5e-4, 0.5)],
+                         ids=["3x15", "5x32", "10x40"])
+def test_both_kernel_families_train_alike(widths, H, W, steps, lr, tol):
+    """Whole fits, loss falling by an order of magnitude, with the split-precision and the fp32 kernels from the same start:
+    the losses stay together at every quarter of the schedule (shallow models: to 1e-3; a 10-layer sine network amplifies
+    any rounding difference over hundreds of Adam steps, so there the two must only reach the same quality)."""
+    import torch
+    n = 6
+    tgt = torch.from_numpy(synth.images(3, n, H, W)).cuda()
+    traj = {}
+    for name, fp32 in FAMILIES.items():
+        f = rinr_fit.Fit(widths, n, H, W, fp32=fp32)
+        f.set_params(synth.init_params(9, widths, n))
+        first, _ = f.loss_grad(tgt, want_grad=False)
+        stages = []
+        for k in range(4):
+            f.steps(tgt, steps // 4, lr, t0=k * (steps // 4), T=steps)
+            stages.append(f.last_loss().copy())
+        traj[name] = np.array(stages)
+        assert np.isfinite(traj[name]).all()
+        assert np.all(traj[name][-1] < 0.2 * first), (name, first, traj[name][-1])
+        f.close()
+    rel = np.abs(traj["split16"] - traj["fp32"]) / traj["fp32"]
+    assert rel.max() <= tol, rel.max(axis=1)
+
+
 def test_fit_prune_quantise_pack_decode_round_trip():
     import torch
     widths, H, W, n = [2, 24, 24, 24, 3], 24, 24, 8
